@@ -1,0 +1,174 @@
+/*
+ * moe_hip.h - C ABI of the MI355X (gfx950) Mixture-of-Experts layer library.
+ *
+ * One GPU's MoE layer, forward and backward, as described in
+ * "Scalable and Efficient MoE Training for Multitask Multilingual Models"
+ * (arXiv 2109.10465): a top-1 / top-2 softmax gate with a per-expert capacity
+ * and Random-Token-Selection priority (Sec. 3.1, Sec. 5.1 "MoE setting"),
+ * dispatch of the flattened [T = batch*seq, d_model] token tensor into
+ * fixed-shape per-expert buffers (Sec. 3.1), the per-expert two-matmul
+ * feed-forward block (Sec. 4.2 "Model details", Sec. 2.3), and the gate-weighted
+ * combine.  The layer arguments mirror the paper's layer statement
+ * MoE(hidden_size, expert, num_experts) (Sec. 2.4) plus k and the capacity.
+ *
+ * Conventions, valid for every entry point unless stated otherwise
+ * ---------------------------------------------------------------
+ *  - Every pointer is a DEVICE pointer owned by the caller.  The library
+ *    allocates nothing, keeps no state between calls and frees nothing.
+ *    Scratch memory comes from the caller through (ws, ws_bytes); ask
+ *    moe_workspace_bytes() for the size.  ws must be 256-byte aligned.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    A call enqueues its kernels on that stream and returns without
+ *    synchronising.  Calls on one stream execute in order; calls that share a
+ *    workspace must not overlap.
+ *  - All arrays are dense and row-major with the shapes given below.
+ *    Activation tensors (x, xd, z, h, yd, y, dy, dyd, dxd, dx) and the expert
+ *    weights W1, W2 have the element type shape->dtype (MOE_F32: float,
+ *    MOE_BF16: bfloat16 as uint16_t bit patterns).  Gate logits, probabilities,
+ *    gate weights, RTS keys, dlogits, dgate_w, Wg, dWg, dW1 and dW2 are always
+ *    float; indices are int32_t.  All accumulation is in fp32.
+ *  - Outputs are overwritten, never accumulated into (the one exception,
+ *    dx_accum, is named so).  Results are bit-reproducible run to run: no
+ *    floating-point atomics are used.
+ *  - Rows s >= expert_count[e] of the per-expert buffers xd, z, h, yd, dyd, dxd
+ *    are never read by any entry point and are left unwritten.
+ *  - Return value: MOE_OK (0) or a negative moe_status.  Argument errors are
+ *    detected on the host before anything is enqueued, so outputs are
+ *    untouched.  Non-finite logits or keys give undefined routing (no fault).
+ *  - Shape limits: T, d_model, d_ff, E, capacity >= 1; k in {1,2}; E >= k;
+ *    E <= 256; d_model and d_ff multiples of 8; T*k and E*capacity < 2^30.
+ */
+#ifndef MOE_HIP_H
+#define MOE_HIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum moe_dtype { MOE_F32 = 0, MOE_BF16 = 1 };
+enum moe_act { MOE_RELU = 0, MOE_GELU = 1 }; /* gelu(z) = z/2 (1 + erf(z/sqrt 2)) */
+
+enum moe_status {
+    MOE_OK = 0,
+    MOE_ERR_NULL = -1,      /* a required pointer is NULL */
+    MOE_ERR_SHAPE = -2,     /* shape outside the limits above */
+    MOE_ERR_DTYPE = -3,     /* unknown dtype or activation */
+    MOE_ERR_WORKSPACE = -4, /* ws NULL, misaligned or smaller than needed */
+    MOE_ERR_LAUNCH = -5     /* the HIP runtime refused a launch */
+};
+
+/* T tokens, d_model, d_ff, E experts, k experts per token, capacity = slots per
+ * expert (C).  The same struct is passed to every call of one layer step. */
+typedef struct {
+    int32_t T, d_model, d_ff, E, k, capacity;
+    int32_t dtype; /* moe_dtype */
+    int32_t act;   /* moe_act   */
+} moe_shape;
+
+/* Human-readable name of a status code (static string, host). */
+const char* moe_status_string(int status);
+
+/* Slots per expert for a capacity factor: max(1, ceil(k*cf*T/E)) (Sec. 5.1:
+ * capacity factor 1.0 for training, 2.0 for evaluation; Sec. 2.3: tokens per
+ * expert depend on batch, experts and top-1 vs top-2).  Host function; returns
+ * -1 on invalid arguments.  The capacity is an explicit input of every other
+ * call, so a caller may use another rule. */
+int32_t moe_capacity(int32_t T, int32_t E, int32_t k, double capacity_factor);
+
+/* Bytes of scratch that the largest user among the entry points needs for
+ * this shape (host function; 0 on an invalid shape). */
+size_t moe_workspace_bytes(const moe_shape* shape);
+
+/* Gate projection (Sec. 3.2: the gating layer is a matrix with one column per
+ * expert):  logits[T,E] = x[T,d_model] * Wg[d_model,E] (+ bias[E]).
+ * bias_or_null exists only to synthesise skewed routing; the paper's gate has
+ * no bias. */
+int moe_gate_logits(const moe_shape* shape, const void* x, const float* Wg,
+                    const float* bias_or_null, float* logits, void* stream);
+
+/* Gate + capacity assignment (Sec. 5.1 top-1 / top-2 gating; Sec. 3.1 expert
+ * capacity and Random Token Selection).
+ *   probs[T,E]      = softmax over experts of logits[T,E]
+ *   expert_idx[T,k] = the k experts with the largest logits, best first; equal
+ *                     logits -> smaller expert id
+ *   gate_w[T,k]     = k=1: probs[t,e0];  k=2: probs[t,e_j]/(probs[t,e0]+probs[t,e1])
+ *   Candidates (t,j) of one expert are ordered by (j ascending, rts_keys[t]
+ *   descending, t ascending); the candidate of rank r gets slot r if r <
+ *   capacity, else it is dropped.  rts_keys_or_null == NULL means equal keys:
+ *   position priority, i.e. tokens at the end of the batch are dropped first.
+ *   slot[T,k]        = slot inside expert expert_idx[t,j], or -1 if dropped
+ *   expert_demand[E] = number of candidates of each expert
+ *   expert_count[E]  = min(capacity, expert_demand) = rows in use
+ *   slot_src[E,C]    = t*k+j of the candidate in that slot, -1 if unused
+ * Needs workspace. */
+int moe_gate_route(const moe_shape* shape, const float* logits, const float* rts_keys_or_null,
+                   float* probs, int32_t* expert_idx, float* gate_w, int32_t* slot,
+                   int32_t* expert_count, int32_t* expert_demand, int32_t* slot_src,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* Dispatch (Sec. 3.1: fixed-shape per-expert buffers):
+ *   xd[e,s,:] = x[slot_src[e,s] / k, :]  for s < expert_count[e]  (bit copies).
+ * Its backward is moe_combine_fwd with gate_w_or_null == NULL. */
+int moe_dispatch(const moe_shape* shape, const void* x, const int32_t* slot_src,
+                 const int32_t* expert_count, void* xd, void* stream);
+
+/* Expert feed-forward block, forward (Sec. 4.2: d_model -> d_ff -> d_model;
+ * Sec. 2.3: the per-expert matmuls carry the compute).  For every expert e and
+ * its first n_e = expert_count[e] rows:
+ *   z = xd_e * W1_e      (W1[E,d_model,d_ff])      -> z_saved[E,C,d_ff]
+ *   h = act(z)                                      -> h_saved[E,C,d_ff]
+ *   yd_e = h * W2_e      (W2[E,d_ff,d_model])      -> yd[E,C,d_model]
+ * No biases.  z_saved and h_saved are kept by the caller for the backward. */
+int moe_expert_ffn_fwd(const moe_shape* shape, const void* xd, const int32_t* expert_count,
+                       const void* W1, const void* W2, void* z_saved, void* h_saved, void* yd,
+                       void* stream);
+
+/* Combine (the mixture itself; a token dropped by every chosen expert gets a
+ * zero row and is carried by the residual connection around the layer,
+ * Sec. 4.2 / Sec. 3.1):
+ *   y[t,:] = sum over j with slot[t,j] >= 0 of gate_w[t,j] * yd[expert_idx[t,j], slot[t,j], :]
+ * gate_w_or_null == NULL uses unit weights (that is dispatch's backward). */
+int moe_combine_fwd(const moe_shape* shape, const void* yd, const int32_t* expert_idx,
+                    const int32_t* slot, const float* gate_w_or_null, void* y, void* stream);
+
+/* Combine, backward.  For kept (t,j), with e = expert_idx[t,j], s = slot[t,j]:
+ *   dyd[e,s,:]   = gate_w[t,j] * dy[t,:]
+ *   dgate_w[t,j] = <dy[t,:], yd[e,s,:]>          (0 for a dropped choice) */
+int moe_combine_bwd(const moe_shape* shape, const void* dy, const void* yd,
+                    const int32_t* expert_idx, const int32_t* slot, const float* gate_w,
+                    void* dyd, float* dgate_w, void* stream);
+
+/* Expert feed-forward block, backward.  Per expert, over its first n_e rows:
+ *   dh = dyd * W2^T,  dz = dh .* act'(z),  dW2 = h^T * dyd,
+ *   dxd = dz * W1^T,  dW1 = xd^T * dz.
+ * dW1[E,d_model,d_ff] and dW2[E,d_ff,d_model] are float; an expert with no
+ * rows gets zero weight gradients.  Needs workspace (holds dz). */
+int moe_expert_ffn_bwd(const moe_shape* shape, const void* dyd, const void* xd,
+                       const void* z_saved, const void* h_saved, const int32_t* expert_count,
+                       const void* W1, const void* W2, void* dxd, float* dW1, float* dW2,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* Gate, backward (selection and slots are constants):  with dg_j = dgate_w[t,j]
+ * for kept choices and 0 for dropped ones,
+ *   k=1: dp[t,e0] = dg_0
+ *   k=2: S = p[t,e0]+p[t,e1]; dp[t,e0] = p[t,e1](dg_0-dg_1)/S^2; dp[t,e1] = p[t,e0](dg_1-dg_0)/S^2
+ *   dlogits[t,e] = p[t,e] * (dp[t,e] - sum_e' p[t,e'] dp[t,e'])       -> dlogits[T,E] */
+int moe_gate_bwd(const moe_shape* shape, const float* dgate_w, const float* probs,
+                 const int32_t* expert_idx, const int32_t* slot, float* dlogits, void* stream);
+
+/* Gate projection, backward:
+ *   dWg[d_model,E]  = x^T * dlogits                       (overwritten)
+ *   dx_accum[T,d]  += dlogits * Wg^T                      (ACCUMULATED into the
+ *   caller's dx, which already holds dispatch's backward; pass NULL to skip).
+ * Needs workspace. */
+int moe_gate_logits_bwd(const moe_shape* shape, const void* x, const float* Wg,
+                        const float* dlogits, float* dWg, void* dx_accum,
+                        void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_HIP_H */

@@ -1,0 +1,155 @@
+"""ctypes binding of libmoe_hip.so: same names as the C ABI (include/moe_hip.h).
+
+Argument marshalling only.  Tensors are torch CUDA tensors used as device
+memory; every call enqueues on torch's current stream unless `stream` is given.
+There is no fallback: if the library has not been built, importing a symbol
+raises.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_hip.so")
+
+F32, BF16 = 0, 1
+RELU, GELU = 0, 1
+
+EXPORTS = [
+    "moe_status_string", "moe_capacity", "moe_workspace_bytes", "moe_gate_logits", "moe_gate_route",
+    "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine_fwd", "moe_combine_bwd", "moe_expert_ffn_bwd",
+    "moe_gate_bwd", "moe_gate_logits_bwd",
+]
+
+
+class MoeShape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("T", "d_model", "d_ff", "E", "k", "capacity", "dtype", "act")]
+
+
+class MoeError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; built with `python -m paper_2109_10465_amd.build`."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise MoeError(f"{LIB_PATH} is missing: build it with `python -m paper_2109_10465_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
+        shp = ctypes.POINTER(MoeShape)
+        L.moe_status_string.restype = ctypes.c_char_p
+        L.moe_status_string.argtypes = [ctypes.c_int]
+        L.moe_capacity.restype = i32
+        L.moe_capacity.argtypes = [i32, i32, i32, ctypes.c_double]
+        L.moe_workspace_bytes.restype = sz
+        L.moe_workspace_bytes.argtypes = [shp]
+        sigs = {
+            "moe_gate_logits": [shp] + [vp] * 5,
+            "moe_gate_route": [shp] + [vp] * 10 + [sz, vp],
+            "moe_dispatch": [shp] + [vp] * 5,
+            "moe_expert_ffn_fwd": [shp] + [vp] * 8,
+            "moe_combine_fwd": [shp] + [vp] * 6,
+            "moe_combine_bwd": [shp] + [vp] * 8,
+            "moe_expert_ffn_bwd": [shp] + [vp] * 11 + [sz, vp],
+            "moe_gate_bwd": [shp] + [vp] * 6,
+            "moe_gate_logits_bwd": [shp] + [vp] * 6 + [sz, vp],
+        }
+        for name, args in sigs.items():
+            fn = getattr(L, name)
+            fn.restype = ctypes.c_int
+            fn.argtypes = args
+        _lib = L
+    return _lib
+
+
+def make_shape(T, d_model, d_ff, E, k, capacity, dtype, act):
+    return MoeShape(T, d_model, d_ff, E, k, capacity, dtype, act)
+
+
+def _p(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise MoeError(f"{what}: {lib().moe_status_string(rc).decode()} ({rc})")
+
+
+def moe_status_string(status):
+    return lib().moe_status_string(status).decode()
+
+
+def moe_capacity(T, E, k, capacity_factor):
+    return lib().moe_capacity(T, E, k, capacity_factor)
+
+
+def moe_workspace_bytes(shape):
+    return lib().moe_workspace_bytes(ctypes.byref(shape))
+
+
+def moe_gate_logits(shape, x, Wg, bias, logits, stream=None):
+    _check(lib().moe_gate_logits(ctypes.byref(shape), _p(x), _p(Wg), _p(bias), _p(logits),
+                                 _stream(stream)), "moe_gate_logits")
+
+
+def moe_gate_route(shape, logits, rts_keys, probs, expert_idx, gate_w, slot, expert_count,
+                   expert_demand, slot_src, ws, stream=None):
+    _check(lib().moe_gate_route(ctypes.byref(shape), _p(logits), _p(rts_keys), _p(probs),
+                                _p(expert_idx), _p(gate_w), _p(slot), _p(expert_count),
+                                _p(expert_demand), _p(slot_src), _p(ws),
+                                0 if ws is None else ws.numel() * ws.element_size(),
+                                _stream(stream)), "moe_gate_route")
+
+
+def moe_dispatch(shape, x, slot_src, expert_count, xd, stream=None):
+    _check(lib().moe_dispatch(ctypes.byref(shape), _p(x), _p(slot_src), _p(expert_count), _p(xd),
+                              _stream(stream)), "moe_dispatch")
+
+
+def moe_expert_ffn_fwd(shape, xd, expert_count, W1, W2, z_saved, h_saved, yd, stream=None):
+    _check(lib().moe_expert_ffn_fwd(ctypes.byref(shape), _p(xd), _p(expert_count), _p(W1), _p(W2),
+                                    _p(z_saved), _p(h_saved), _p(yd), _stream(stream)),
+           "moe_expert_ffn_fwd")
+
+
+def moe_combine_fwd(shape, yd, expert_idx, slot, gate_w, y, stream=None):
+    _check(lib().moe_combine_fwd(ctypes.byref(shape), _p(yd), _p(expert_idx), _p(slot), _p(gate_w),
+                                 _p(y), _stream(stream)), "moe_combine_fwd")
+
+
+def moe_combine_bwd(shape, dy, yd, expert_idx, slot, gate_w, dyd, dgate_w, stream=None):
+    _check(lib().moe_combine_bwd(ctypes.byref(shape), _p(dy), _p(yd), _p(expert_idx), _p(slot),
+                                 _p(gate_w), _p(dyd), _p(dgate_w), _stream(stream)),
+           "moe_combine_bwd")
+
+
+def moe_expert_ffn_bwd(shape, dyd, xd, z_saved, h_saved, expert_count, W1, W2, dxd, dW1, dW2, ws,
+                       stream=None):
+    _check(lib().moe_expert_ffn_bwd(ctypes.byref(shape), _p(dyd), _p(xd), _p(z_saved), _p(h_saved),
+                                    _p(expert_count), _p(W1), _p(W2), _p(dxd), _p(dW1), _p(dW2),
+                                    _p(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                    _stream(stream)), "moe_expert_ffn_bwd")
+
+
+def moe_gate_bwd(shape, dgate_w, probs, expert_idx, slot, dlogits, stream=None):
+    _check(lib().moe_gate_bwd(ctypes.byref(shape), _p(dgate_w), _p(probs), _p(expert_idx), _p(slot),
+                              _p(dlogits), _stream(stream)), "moe_gate_bwd")
+
+
+def moe_gate_logits_bwd(shape, x, Wg, dlogits, dWg, dx_accum, ws, stream=None):
+    _check(lib().moe_gate_logits_bwd(ctypes.byref(shape), _p(x), _p(Wg), _p(dlogits), _p(dWg),
+                                     _p(dx_accum), _p(ws),
+                                     0 if ws is None else ws.numel() * ws.element_size(),
+                                     _stream(stream)), "moe_gate_logits_bwd")

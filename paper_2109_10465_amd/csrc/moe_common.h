@@ -1,0 +1,115 @@
+// Shared device/host helpers for the MoE kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/moe_hip.h"
+
+#define MOE_WAVE 64
+
+typedef uint16_t bf16_t;  // bfloat16 bit pattern
+
+// ---- bf16 <-> fp32 ---------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) {
+    return __uint_as_float(((uint32_t)v) << 16);
+}
+// round to nearest, ties to even (finite inputs; NaN stays NaN)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// element-type generic scalar load/store through fp32
+template <typename T> __device__ __forceinline__ float ld_f32(const T* p);
+template <> __device__ __forceinline__ float ld_f32<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float ld_f32<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ __forceinline__ void st_f32(T* p, float v);
+template <> __device__ __forceinline__ void st_f32<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void st_f32<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// A 16-byte chunk of activations: 4 floats or 8 bf16, widened to fp32 lanes.
+template <typename T> struct Chunk;
+template <> struct Chunk<float> {
+    static constexpr int N = 4;
+    __device__ static __forceinline__ void load(const float* p, float (&v)[4]) {
+        float4 q = *reinterpret_cast<const float4*>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    }
+    __device__ static __forceinline__ void store(float* p, const float (&v)[4]) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <> struct Chunk<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+        uint4 q = *reinterpret_cast<const uint4*>(p);
+        uint32_t w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+        uint4 q;
+        q.x = pack_bf16x2(v[0], v[1]); q.y = pack_bf16x2(v[2], v[3]);
+        q.z = pack_bf16x2(v[4], v[5]); q.w = pack_bf16x2(v[6], v[7]);
+        *reinterpret_cast<uint4*>(p) = q;
+    }
+};
+
+// ---- wave64 reductions (butterfly: every lane ends with the same bits) ------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, MOE_WAVE);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, MOE_WAVE));
+    return v;
+}
+__device__ __forceinline__ int wave_sum_i(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, MOE_WAVE);
+    return v;
+}
+
+// ---- activation (Sec. 4.2 feed-forward block; exact erf GeLU) ---------------
+__device__ __forceinline__ float act_fwd(float z, int act) {
+    if (act == MOE_RELU) return fmaxf(z, 0.0f);
+    return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float act_bwd(float z, int act) {
+    if (act == MOE_RELU) return z > 0.0f ? 1.0f : 0.0f;
+    const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
+    const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
+    return cdf + z * pdf;
+}
+
+// ---- host-side helpers -------------------------------------------------------
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+static inline size_t elem_bytes(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
+
+// Validates the shape limits documented in moe_hip.h.
+static inline int check_shape(const moe_shape* s) {
+    if (!s) return MOE_ERR_NULL;
+    if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_DTYPE;
+    if (s->act != MOE_RELU && s->act != MOE_GELU) return MOE_ERR_DTYPE;
+    if (s->T < 1 || s->d_model < 1 || s->d_ff < 1 || s->E < 1 || s->capacity < 1) return MOE_ERR_SHAPE;
+    if (s->k < 1 || s->k > 2 || s->E < s->k || s->E > 256) return MOE_ERR_SHAPE;
+    if (s->d_model % 8 || s->d_ff % 8) return MOE_ERR_SHAPE;
+    if ((int64_t)s->T * s->k >= (1 << 30) || (int64_t)s->E * s->capacity >= (1 << 30)) return MOE_ERR_SHAPE;
+    return MOE_OK;
+}
+static inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
+
+// Workspace layouts (bytes), shared by moe_workspace_bytes and the entry points.
+size_t route_ws_bytes(const moe_shape* s);
+size_t ffn_bwd_ws_bytes(const moe_shape* s);
+size_t gate_logits_bwd_ws_bytes(const moe_shape* s);

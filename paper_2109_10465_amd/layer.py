@@ -1,0 +1,82 @@
+"""Buffer owner and call sequence for one MoE layer step on one GPU.
+
+Holds the device buffers (torch tensors used as raw memory) and issues the
+C-ABI calls in the order gate -> capacity/RTS -> dispatch -> experts -> combine
+(forward) and its reverse (backward).  No arithmetic happens here.
+"""
+import torch
+
+from . import binding as B
+
+_TORCH_DT = {B.F32: torch.float32, B.BF16: torch.bfloat16}
+
+
+class MoELayer:
+    def __init__(self, T, d_model, d_ff, E, k, capacity, dtype, act, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise B.MoeError("MoELayer needs a GPU; there is no CPU fallback")
+        B.lib()
+        self.shape = B.make_shape(T, d_model, d_ff, E, k, capacity, dtype, act)
+        self.T, self.d, self.f, self.E, self.k, self.C = T, d_model, d_ff, E, k, capacity
+        self.device = torch.device(device)
+        adt = _TORCH_DT[dtype]
+        dev = self.device
+
+        def buf(shape, dt):
+            return torch.empty(shape, dtype=dt, device=dev)
+
+        i32, f32 = torch.int32, torch.float32
+        self.logits = buf((T, E), f32)
+        self.probs = buf((T, E), f32)
+        self.expert_idx = buf((T, k), i32)
+        self.gate_w = buf((T, k), f32)
+        self.slot = buf((T, k), i32)
+        self.expert_count = buf((E,), i32)
+        self.expert_demand = buf((E,), i32)
+        self.slot_src = buf((E, capacity), i32)
+        self.xd = buf((E, capacity, d_model), adt)
+        self.z = buf((E, capacity, d_ff), adt)
+        self.h = buf((E, capacity, d_ff), adt)
+        self.yd = buf((E, capacity, d_model), adt)
+        self.y = buf((T, d_model), adt)
+        # backward
+        self.dyd = buf((E, capacity, d_model), adt)
+        self.dgate_w = buf((T, k), f32)
+        self.dxd = buf((E, capacity, d_model), adt)
+        self.dW1 = buf((E, d_model, d_ff), f32)
+        self.dW2 = buf((E, d_ff, d_model), f32)
+        self.dlogits = buf((T, E), f32)
+        self.dWg = buf((d_model, E), f32)
+        self.dx = buf((T, d_model), adt)
+        nbytes = B.moe_workspace_bytes(self.shape)
+        if nbytes == 0:
+            raise B.MoeError("unsupported shape")
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    def forward(self, x, Wg, bias, W1, W2, rts_keys):
+        s = self.shape
+        self._saved = (x, Wg, W1, W2)
+        B.moe_gate_logits(s, x, Wg, bias, self.logits)
+        B.moe_gate_route(s, self.logits, rts_keys, self.probs, self.expert_idx, self.gate_w,
+                         self.slot, self.expert_count, self.expert_demand, self.slot_src, self.ws)
+        B.moe_dispatch(s, x, self.slot_src, self.expert_count, self.xd)
+        B.moe_expert_ffn_fwd(s, self.xd, self.expert_count, W1, W2, self.z, self.h, self.yd)
+        B.moe_combine_fwd(s, self.yd, self.expert_idx, self.slot, self.gate_w, self.y)
+        return self.y
+
+    def backward(self, dy):
+        s = self.shape
+        x, Wg, W1, W2 = self._saved
+        B.moe_combine_bwd(s, dy, self.yd, self.expert_idx, self.slot, self.gate_w, self.dyd,
+                          self.dgate_w)
+        B.moe_expert_ffn_bwd(s, self.dyd, self.xd, self.z, self.h, self.expert_count, W1, W2,
+                             self.dxd, self.dW1, self.dW2, self.ws)
+        # dispatch's backward = combine with unit weights
+        B.moe_combine_fwd(s, self.dxd, self.expert_idx, self.slot, None, self.dx)
+        B.moe_gate_bwd(s, self.dgate_w, self.probs, self.expert_idx, self.slot, self.dlogits)
+        B.moe_gate_logits_bwd(s, x, Wg, self.dlogits, self.dWg, self.dx, self.ws)
+        return self.dx, self.dWg, self.dW1, self.dW2
+
+    def step(self, x, Wg, bias, W1, W2, rts_keys, dy):
+        self.forward(x, Wg, bias, W1, W2, rts_keys)
+        return self.backward(dy)
