@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of one GPU's MoE layer, forward + backward, on seeded synthetic input.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
+
+A step is one pass of the whole hot path over one batch resident in HBM: gate
+projection, softmax/top-k/capacity+RTS routing, dispatch, expert FFN forward,
+combine, then combine backward, expert FFN backward, dispatch backward, gate
+backward and gate-projection backward.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA = 2.5e15      # dense bf16 MFMA, FLOP/s (MI355X datasheet)
+PEAK_F32_MFMA = 157.3e12     # fp32 matrix
+PEAK_HBM = 8.0e12            # B/s
+
+
+def cpu_baseline(w, d, budget_flops=2.0e12):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload:
+    the first Ts tokens (all of them if the whole layer is below ~2e12 flop),
+    capacity scaled with Ts.  Timed on this host's cores."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import moe_oracle as O
+    full = 12.0 * w.k * w.T * w.d_model * w.d_ff
+    Ts = w.T if full <= budget_flops else max(w.E * 8, int(w.T * budget_flops / full))
+    C = w.capacity if Ts == w.T else O.capacity(Ts, w.E, w.k, w.capacity_factor)
+    t0 = time.time()
+    O.moe_layer(d["x"][:Ts], d["Wg"], d["bias"], d["W1"], d["W2"], d["rts_keys"][:Ts], d["dy"][:Ts],
+                w.k, C, w.act)
+    dt = time.time() - t0
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": Ts / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"first {Ts} of {w.T} tokens, all {w.E} experts, capacity {C}, fwd+bwd in fp64, "
+                      f"{dt:.1f} s on {os.cpu_count()} visible cpus"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also print per-call timings to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2109_10465_amd import binding as B
+    from paper_2109_10465_amd import inputs as I
+    from paper_2109_10465_amd.layer import MoELayer
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    B.lib()
+    w = I.WORKLOADS[args.workload]
+    d = I.make_inputs(w, seed=0)
+    adt = torch.bfloat16 if w.dtype == I.BF16 else torch.float32
+
+    def dev(a, dt=torch.float32):
+        return None if a is None else torch.from_numpy(a).cuda().to(dt)
+
+    x, dy, W1, W2 = dev(d["x"], adt), dev(d["dy"], adt), dev(d["W1"], adt), dev(d["W2"], adt)
+    Wg, bias, keys = dev(d["Wg"]), dev(d["bias"]), dev(d["rts_keys"])
+    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act)
+    s = layer.shape
+    L = layer
+
+    calls = [
+        ("gate_logits", lambda: B.moe_gate_logits(s, x, Wg, bias, L.logits)),
+        ("gate_route", lambda: B.moe_gate_route(s, L.logits, keys, L.probs, L.expert_idx, L.gate_w, L.slot,
+                                                L.expert_count, L.expert_demand, L.slot_src, L.ws)),
+        ("dispatch", lambda: B.moe_dispatch(s, x, L.slot_src, L.expert_count, L.xd)),
+        ("expert_ffn_fwd", lambda: B.moe_expert_ffn_fwd(s, L.xd, L.expert_count, W1, W2, L.z, L.h, L.yd)),
+        ("combine_fwd", lambda: B.moe_combine_fwd(s, L.yd, L.expert_idx, L.slot, L.gate_w, L.y)),
+        ("combine_bwd", lambda: B.moe_combine_bwd(s, dy, L.yd, L.expert_idx, L.slot, L.gate_w, L.dyd, L.dgate_w)),
+        ("expert_ffn_bwd", lambda: B.moe_expert_ffn_bwd(s, L.dyd, L.xd, L.z, L.h, L.expert_count, W1, W2,
+                                                        L.dxd, L.dW1, L.dW2, L.ws)),
+        ("dispatch_bwd", lambda: B.moe_combine_fwd(s, L.dxd, L.expert_idx, L.slot, None, L.dx)),
+        ("gate_bwd", lambda: B.moe_gate_bwd(s, L.dgate_w, L.probs, L.expert_idx, L.slot, L.dlogits)),
+        ("gate_logits_bwd", lambda: B.moe_gate_logits_bwd(s, x, Wg, L.dlogits, L.dWg, L.dx, L.ws)),
+    ]
+    gemm_calls = {"expert_ffn_fwd", "expert_ffn_bwd"}
+
+    for _ in range(args.warmup):
+        for _, fn in calls:
+            fn()
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; HIP events (torch's current stream is the
+    # stream the kernels are launched on) bracket the expert-GEMM calls
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        e = iter(ev[i])
+        for name, fn in calls:
+            if name in gemm_calls:
+                next(e).record()
+                fn()
+                next(e).record()
+            else:
+                fn()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    gemm_ms = sum(a.elapsed_time(b) + c.elapsed_time(dd) for a, b, c, dd in ev) / args.steps
+
+    M = int(L.expert_count.sum().item())                      # kept assignments actually routed
+    flops = 12.0 * M * w.d_model * w.d_ff                     # 6 grouped GEMMs, 2*M*d*f each
+    peak = PEAK_BF16_MFMA if w.dtype == I.BF16 else PEAK_F32_MFMA
+    achieved = flops / (gemm_ms * 1e-3)
+    roofline = {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step)",
+                "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
+                "frac": achieved / peak, "traffic": None,
+                "flops_per_launch": flops / 6.0, "avg_launch_ms": gemm_ms / 6.0,
+                "kept_assignments": M}
+
+    breakdown = None
+    if args.breakdown:
+        n = len(calls)
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(n + 1)] for _ in range(args.steps)]
+        for i in range(args.steps):
+            for j, (_, fn) in enumerate(calls):
+                evs[i][j].record()
+                fn()
+            evs[i][n].record()
+        torch.cuda.synchronize()
+        breakdown = {}
+        for j, (name, _) in enumerate(calls):
+            ts = sorted(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps))
+            breakdown[name] = {"median_us": ts[len(ts) // 2] * 1e3, "min_us": ts[0] * 1e3}
+        sb = 2 if w.dtype == I.BF16 else 4
+        Tn, dm, E, k, C = w.T, w.d_model, w.E, w.k, w.capacity
+        kept_tok = int((L.slot >= 0).any(dim=1).sum().item())
+        alg = {   # algorithmic HBM bytes per call
+            "gate_logits": Tn * dm * sb + dm * E * 4 + Tn * E * 4,
+            "gate_route": Tn * E * 4 * 2 + 12 * Tn * k + 4 * Tn + 4 * Tn * k + 4 * E * C + 8 * E,
+            "dispatch": kept_tok * dm * sb + 4 * E * C + M * dm * sb,
+            "combine_fwd": M * dm * sb + 12 * Tn * k + Tn * dm * sb,
+            "combine_bwd": Tn * dm * sb + M * dm * sb + M * dm * sb + 4 * Tn * k,
+            "dispatch_bwd": M * dm * sb + 8 * Tn * k + Tn * dm * sb,
+            "gate_bwd": Tn * E * 4 * 2 + 16 * Tn * k,
+            "gate_logits_bwd": 2 * Tn * dm * sb + Tn * E * 4 + Tn * dm * sb + dm * E * 8,
+        }
+        for name, b in alg.items():
+            us = breakdown[name]["median_us"]
+            breakdown[name]["alg_MB"] = b / 1e6
+            breakdown[name]["GBps"] = b / (us * 1e-6) / 1e9
+            breakdown[name]["hbm_frac"] = b / (us * 1e-6) / PEAK_HBM
+        for name, fl in (("expert_ffn_fwd", 4.0), ("expert_ffn_bwd", 8.0)):
+            us = breakdown[name]["median_us"]
+            breakdown[name]["TFLOPs"] = fl * M * dm * w.d_ff / (us * 1e-6) / 1e12
+            breakdown[name]["mfma_frac"] = fl * M * dm * w.d_ff / (us * 1e-6) / peak
+        for name, v in breakdown.items():
+            print(f"[breakdown] {name:16s} " + " ".join(f"{k}={val:.4g}" for k, val in v.items()), file=sys.stderr)
+
+    out = {
+        "metric": "MoE layer fwd+bwd tokens/sec on 1 MI355X",
+        "value": w.T / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == I.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "T": w.T, "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k,
+                   "capacity": w.capacity, "capacity_factor": w.capacity_factor,
+                   "act": "gelu" if w.act == I.GELU else "relu", "kept_assignments": M,
+                   "expert_demand_max": int(L.expert_demand.max().item()),
+                   "expert_demand_min": int(L.expert_demand.min().item())},
+        "roofline": roofline,
+    }
+    if breakdown is not None:
+        out["breakdown"] = breakdown
+    if not args.no_cpu_baseline:
+        del x, dy, W1, W2, layer, L
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w, d)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

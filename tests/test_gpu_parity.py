@@ -102,8 +102,10 @@ def test_duplicate_keys_fall_back_to_token_order():
 
 
 def test_combine_of_dispatch_with_unit_weights_is_identity_on_kept_tokens():
-    w = I.small("identity", 1200, 96, 64, 6, 2, 250, I.BF16)
+    w = I.small("identity", 1200, 96, 64, 6, 2, 150, I.BF16, skew="hot0", skew_param=0.6)
     d = I.make_inputs(w, seed=17)
+    d["Wg"] = d["Wg"] * 8.0
+    d["bias"] = d["bias"] * 8.0
     layer, got = G.run_layer(w, d)
     x = G.to_dev(d["x"], w.dtype)
     back = torch.empty_like(x)
