@@ -82,10 +82,10 @@ def main():
         ("gate_route", lambda: B.moe_gate_route(s, L.logits, keys, L.probs, L.expert_idx, L.gate_w, L.slot,
                                                 L.expert_count, L.expert_demand, L.slot_src, L.ws)),
         ("dispatch", lambda: B.moe_dispatch(s, x, L.slot_src, L.expert_count, L.xd)),
-        ("expert_ffn_fwd", lambda: B.moe_expert_ffn_fwd(s, L.xd, L.expert_count, W1, W2, L.z, L.h, L.yd)),
+        ("expert_ffn_fwd", lambda: B.moe_expert_ffn_fwd(s, L.xd, L.expert_count, W1, W2, L.h, L.dact, L.yd)),
         ("combine_fwd", lambda: B.moe_combine_fwd(s, L.yd, L.expert_idx, L.slot, L.gate_w, L.y)),
         ("combine_bwd", lambda: B.moe_combine_bwd(s, dy, L.yd, L.expert_idx, L.slot, L.gate_w, L.dyd, L.dgate_w)),
-        ("expert_ffn_bwd", lambda: B.moe_expert_ffn_bwd(s, L.dyd, L.xd, L.z, L.h, L.expert_count, W1, W2,
+        ("expert_ffn_bwd", lambda: B.moe_expert_ffn_bwd(s, L.dyd, L.xd, L.h, L.dact, L.expert_count, W1, W2,
                                                         L.dxd, L.dW1, L.dW2, L.ws)),
         ("dispatch_bwd", lambda: B.moe_combine_fwd(s, L.dxd, L.expert_idx, L.slot, None, L.dx)),
         ("gate_bwd", lambda: B.moe_gate_bwd(s, L.dgate_w, L.probs, L.expert_idx, L.slot, L.dlogits)),

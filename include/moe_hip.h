@@ -22,7 +22,7 @@
  *    synchronising.  Calls on one stream execute in order; calls that share a
  *    workspace must not overlap.
  *  - All arrays are dense and row-major with the shapes given below.
- *    Activation tensors (x, xd, z, h, yd, y, dy, dyd, dxd, dx) and the expert
+ *    Activation tensors (x, xd, h, dact, yd, y, dy, dyd, dxd, dx) and the expert
  *    weights W1, W2 have the element type shape->dtype (MOE_F32: float,
  *    MOE_BF16: bfloat16 as uint16_t bit patterns).  Gate logits, probabilities,
  *    gate weights, RTS keys, dlogits, dgate_w, Wg, dWg, dW1 and dW2 are always
@@ -30,7 +30,7 @@
  *  - Outputs are overwritten, never accumulated into (the one exception,
  *    dx_accum, is named so).  Results are bit-reproducible run to run: no
  *    floating-point atomics are used.
- *  - Rows s >= expert_count[e] of the per-expert buffers xd, z, h, yd, dyd, dxd
+ *  - Rows s >= expert_count[e] of the per-expert buffers xd, h, dact, yd, dyd, dxd
  *    are never read by any entry point and are left unwritten.
  *  - Return value: MOE_OK (0) or a negative moe_status.  Argument errors are
  *    detected on the host before anything is enqueued, so outputs are
@@ -118,12 +118,15 @@ int moe_dispatch(const moe_shape* shape, const void* x, const int32_t* slot_src,
 /* Expert feed-forward block, forward (Sec. 4.2: d_model -> d_ff -> d_model;
  * Sec. 2.3: the per-expert matmuls carry the compute).  For every expert e and
  * its first n_e = expert_count[e] rows:
- *   z = xd_e * W1_e      (W1[E,d_model,d_ff])      -> z_saved[E,C,d_ff]
+ *   z = xd_e * W1_e      (W1[E,d_model,d_ff])      (not stored)
  *   h = act(z)                                      -> h_saved[E,C,d_ff]
+ *   act'(z)                                         -> dact_saved[E,C,d_ff]
  *   yd_e = h * W2_e      (W2[E,d_ff,d_model])      -> yd[E,C,d_model]
- * No biases.  z_saved and h_saved are kept by the caller for the backward. */
+ * No biases.  relu'(z) = [z > 0]; gelu'(z) = Phi(z) + z phi(z).  h_saved and
+ * dact_saved are kept by the caller for the backward: the activation and its
+ * derivative are both evaluated here, once, while z is in registers. */
 int moe_expert_ffn_fwd(const moe_shape* shape, const void* xd, const int32_t* expert_count,
-                       const void* W1, const void* W2, void* z_saved, void* h_saved, void* yd,
+                       const void* W1, const void* W2, void* h_saved, void* dact_saved, void* yd,
                        void* stream);
 
 /* Combine (the mixture itself; a token dropped by every chosen expert gets a
@@ -142,12 +145,12 @@ int moe_combine_bwd(const moe_shape* shape, const void* dy, const void* yd,
                     void* dyd, float* dgate_w, void* stream);
 
 /* Expert feed-forward block, backward.  Per expert, over its first n_e rows:
- *   dh = dyd * W2^T,  dz = dh .* act'(z),  dW2 = h^T * dyd,
+ *   dh = dyd * W2^T,  dz = dh .* dact_saved,  dW2 = h_saved^T * dyd,
  *   dxd = dz * W1^T,  dW1 = xd^T * dz.
  * dW1[E,d_model,d_ff] and dW2[E,d_ff,d_model] are float; an expert with no
  * rows gets zero weight gradients.  Needs workspace (holds dz). */
 int moe_expert_ffn_bwd(const moe_shape* shape, const void* dyd, const void* xd,
-                       const void* z_saved, const void* h_saved, const int32_t* expert_count,
+                       const void* h_saved, const void* dact_saved, const int32_t* expert_count,
                        const void* W1, const void* W2, void* dxd, float* dW1, float* dW2,
                        void* ws, size_t ws_bytes, void* stream);
 

@@ -118,9 +118,9 @@ def moe_dispatch(shape, x, slot_src, expert_count, xd, stream=None):
                               _stream(stream)), "moe_dispatch")
 
 
-def moe_expert_ffn_fwd(shape, xd, expert_count, W1, W2, z_saved, h_saved, yd, stream=None):
+def moe_expert_ffn_fwd(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, stream=None):
     _check(lib().moe_expert_ffn_fwd(ctypes.byref(shape), _p(xd), _p(expert_count), _p(W1), _p(W2),
-                                    _p(z_saved), _p(h_saved), _p(yd), _stream(stream)),
+                                    _p(h_saved), _p(dact_saved), _p(yd), _stream(stream)),
            "moe_expert_ffn_fwd")
 
 
@@ -135,9 +135,9 @@ def moe_combine_bwd(shape, dy, yd, expert_idx, slot, gate_w, dyd, dgate_w, strea
            "moe_combine_bwd")
 
 
-def moe_expert_ffn_bwd(shape, dyd, xd, z_saved, h_saved, expert_count, W1, W2, dxd, dW1, dW2, ws,
+def moe_expert_ffn_bwd(shape, dyd, xd, h_saved, dact_saved, expert_count, W1, W2, dxd, dW1, dW2, ws,
                        stream=None):
-    _check(lib().moe_expert_ffn_bwd(ctypes.byref(shape), _p(dyd), _p(xd), _p(z_saved), _p(h_saved),
+    _check(lib().moe_expert_ffn_bwd(ctypes.byref(shape), _p(dyd), _p(xd), _p(h_saved), _p(dact_saved),
                                     _p(expert_count), _p(W1), _p(W2), _p(dxd), _p(dW1), _p(dW2),
                                     _p(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                                     _stream(stream)), "moe_expert_ffn_bwd")

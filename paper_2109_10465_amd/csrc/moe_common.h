@@ -19,8 +19,12 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
     u += 0x7fffu + ((u >> 16) & 1u);
     return (bf16_t)(u >> 16);
 }
+// two fp32 -> packed bf16 pair (v_cvt_pk_bf16_f32, round to nearest even)
+typedef __bf16 bf16x2_hw_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+    const f32x2_hw_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw_t));
 }
 
 // element-type generic scalar load/store through fp32
@@ -77,18 +81,6 @@ __device__ __forceinline__ int wave_sum_i(int v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, MOE_WAVE);
     return v;
-}
-
-// ---- activation (Sec. 4.2 feed-forward block; exact erf GeLU) ---------------
-__device__ __forceinline__ float act_fwd(float z, int act) {
-    if (act == MOE_RELU) return fmaxf(z, 0.0f);
-    return 0.5f * z * (1.0f + erff(z * 0.70710678118654752440f));
-}
-__device__ __forceinline__ float act_bwd(float z, int act) {
-    if (act == MOE_RELU) return z > 0.0f ? 1.0f : 0.0f;
-    const float cdf = 0.5f * (1.0f + erff(z * 0.70710678118654752440f));
-    const float pdf = 0.39894228040143267794f * __expf(-0.5f * z * z);
-    return cdf + z * pdf;
 }
 
 // ---- host-side helpers -------------------------------------------------------

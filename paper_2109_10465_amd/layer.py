@@ -35,8 +35,8 @@ class MoELayer:
         self.expert_demand = buf((E,), i32)
         self.slot_src = buf((E, capacity), i32)
         self.xd = buf((E, capacity, d_model), adt)
-        self.z = buf((E, capacity, d_ff), adt)
-        self.h = buf((E, capacity, d_ff), adt)
+        self.h = buf((E, capacity, d_ff), adt)       # act(z)
+        self.dact = buf((E, capacity, d_ff), adt)    # act'(z)
         self.yd = buf((E, capacity, d_model), adt)
         self.y = buf((T, d_model), adt)
         # backward
@@ -60,7 +60,7 @@ class MoELayer:
         B.moe_gate_route(s, self.logits, rts_keys, self.probs, self.expert_idx, self.gate_w,
                          self.slot, self.expert_count, self.expert_demand, self.slot_src, self.ws)
         B.moe_dispatch(s, x, self.slot_src, self.expert_count, self.xd)
-        B.moe_expert_ffn_fwd(s, self.xd, self.expert_count, W1, W2, self.z, self.h, self.yd)
+        B.moe_expert_ffn_fwd(s, self.xd, self.expert_count, W1, W2, self.h, self.dact, self.yd)
         B.moe_combine_fwd(s, self.yd, self.expert_idx, self.slot, self.gate_w, self.y)
         return self.y
 
@@ -69,7 +69,7 @@ class MoELayer:
         x, Wg, W1, W2 = self._saved
         B.moe_combine_bwd(s, dy, self.yd, self.expert_idx, self.slot, self.gate_w, self.dyd,
                           self.dgate_w)
-        B.moe_expert_ffn_bwd(s, self.dyd, self.xd, self.z, self.h, self.expert_count, W1, W2,
+        B.moe_expert_ffn_bwd(s, self.dyd, self.xd, self.h, self.dact, self.expert_count, W1, W2,
                              self.dxd, self.dW1, self.dW2, self.ws)
         # dispatch's backward = combine with unit weights
         B.moe_combine_fwd(s, self.dxd, self.expert_idx, self.slot, None, self.dx)

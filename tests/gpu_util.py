@@ -46,7 +46,7 @@ def run_layer(w, d, use_keys=True):
     layer.step(x, Wg, bias, W1, W2, keys, dy)
     torch.cuda.synchronize()
     names = ["logits", "probs", "expert_idx", "gate_w", "slot", "expert_count", "expert_demand",
-             "slot_src", "xd", "z", "h", "yd", "y", "dyd", "dgate_w", "dxd", "dW1", "dW2",
+             "slot_src", "xd", "h", "dact", "yd", "y", "dyd", "dgate_w", "dxd", "dW1", "dW2",
              "dlogits", "dWg", "dx"]
     out = {n: host(getattr(layer, n)) for n in names}
     return layer, out
@@ -73,7 +73,8 @@ def check_full(w, d, got, use_keys=True):
         errs[n] = rel_l2(got[n], ref[n])
         assert errs[n] <= 1e-5, (n, errs[n])
     m = row_mask(ref["expert_count"], w.capacity)
-    pairs = [("xd", "Xd"), ("z", "Z"), ("h", "H"), ("yd", "Yd"), ("dyd", "dYd"), ("dxd", "dXd")]
+    ref["dact"] = O.act_grad(ref["Z"], w.act)          # the derivative the forward saves
+    pairs = [("xd", "Xd"), ("h", "H"), ("dact", "dact"), ("yd", "Yd"), ("dyd", "dYd"), ("dxd", "dXd")]
     for g, r in pairs:
         errs[g] = rel_l2(got[g][m], ref[r][m])
         assert errs[g] <= tol, (g, errs[g])
@@ -202,7 +203,7 @@ def check_sampled(w, d, got, n_tokens=192, n_cols=24, n_rows=48, seed=0, fetch_e
         xd_e = fetch_expert("xd", e)[:n]
         assert np.array_equal(xd_e, Xd.astype(np.float32))          # bit copies
         upd("dyd", fetch_expert("dyd", e)[:n], dYd)
-        upd("z", fetch_expert("z", e)[:n][:, cols], Zc[:n])
+        upd("dact", fetch_expert("dact", e)[:n][:, cols], O.act_grad(Zc[:n], w.act))
         upd("h", fetch_expert("h", e)[:n][:, cols], Hc[:n])
         rows = np.sort(rng.choice(n, size=min(n_rows, n), replace=False))
         one = np.ones(1, np.int32)

@@ -17,6 +17,7 @@ def full_result(w, d):
     got = {k.lower() if k in ("Xd", "Z", "H", "Yd") else {"dYd": "dyd", "dXd": "dxd"}.get(k, k): v
            for k, v in out.items()}
     got["logits"] = lg
+    got["dact"] = O.act_grad(out["Z"], w.act)
     return got
 
 
@@ -28,7 +29,7 @@ def test_sampled_checker_accepts_the_oracle_and_rejects_planted_errors(k):
     got = full_result(w, d)
     fetch = lambda name, e: got[name][e]
     G.check_sampled(w, d, got, n_tokens=60, n_cols=8, n_rows=10, fetch_expert=fetch)
-    for name in ["y", "dx", "dgate_w", "dlogits", "dW1", "dW2", "yd", "dxd", "dWg", "z"]:
+    for name in ["y", "dx", "dgate_w", "dlogits", "dW1", "dW2", "yd", "dxd", "dWg", "dact"]:
         bad = dict(got)
         bad[name] = got[name] * 1.001 + 1e-3
         with pytest.raises(AssertionError):
