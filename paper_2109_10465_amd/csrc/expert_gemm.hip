@@ -251,46 +251,26 @@ __device__ __forceinline__ void act_both(float z, float& h, float& a) {
     a = cdf + zpdf;
 }
 
-// 4 consecutive elements of one row, as the activation type
-template <typename T> struct Vec4;
-template <> struct Vec4<float> {
-    typedef float4 raw;
-    __device__ static __forceinline__ raw zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
-    __device__ static __forceinline__ raw pack(const float (&v)[4]) { return make_float4(v[0], v[1], v[2], v[3]); }
-    __device__ static __forceinline__ void unpack(raw q, float (&v)[4]) { v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w; }
-};
-template <> struct Vec4<bf16_t> {
-    typedef uint2 raw;
-    __device__ static __forceinline__ raw zero() { return make_uint2(0u, 0u); }
-    __device__ static __forceinline__ raw pack(const float (&v)[4]) {
-        return make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
-    }
-    __device__ static __forceinline__ void unpack(raw q, float (&v)[4]) {
-        v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
-        v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
-    }
-};
-
 // One row vector of the output tile: o = element offset, v = 4 accumulators,
 // aux = the 4 saved derivatives (EPI_MUL only).
 template <typename T, int EPI, int ACT>
 __device__ __forceinline__ void epilogue4(const GemmArgs& p, size_t o, float (&v)[4],
-                                          typename Vec4<T>::raw aux) {
-    typedef typename Vec4<T>::raw raw;
+                                          typename Vec4io<T>::raw aux) {
+    typedef typename Vec4io<T>::raw raw;
     if constexpr (EPI == EPI_STORE) {
-        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4<T>::pack(v);
+        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(v);
     } else if constexpr (EPI == EPI_H_DACT) {
         float h[4], a[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) act_both<sizeof(T) == 2, ACT>(v[i], h[i], a[i]);
-        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4<T>::pack(a);
-        *reinterpret_cast<raw*>((T*)p.out1 + o) = Vec4<T>::pack(h);
+        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(a);
+        *reinterpret_cast<raw*>((T*)p.out1 + o) = Vec4io<T>::pack(h);
     } else if constexpr (EPI == EPI_MUL) {
         float a[4];
-        Vec4<T>::unpack(aux, a);
+        Vec4io<T>::unpack(aux, a);
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] *= a[i];
-        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4<T>::pack(v);
+        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(v);
     } else {
         *reinterpret_cast<float4*>((float*)p.out0 + o) = make_float4(v[0], v[1], v[2], v[3]);
     }
@@ -378,7 +358,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
     const int ncol = n0 + wn * WCOLS + ec;
     // EPI_MUL: the saved derivative does not depend on the product, so it is
     // fetched now and rides in registers through the main loop
-    typename Vec4<T>::raw aux[EPI == EPI_MUL ? TM : 1][EPI == EPI_MUL ? NIT : 1];
+    typename Vec4io<T>::raw aux[EPI == EPI_MUL ? TM : 1][EPI == EPI_MUL ? NIT : 1];
     if constexpr (EPI == EPI_MUL) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -386,8 +366,8 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
             for (int it = 0; it < NIT; ++it) {
                 const int m = m0 + wm * (BM / 2) + i * 32 + er + it * RPI;
                 aux[i][it] = (m < m_lim && ncol < p.N)
-                    ? *reinterpret_cast<const typename Vec4<T>::raw*>((const T*)p.aux + obase + (size_t)m * p.ldo + ncol)
-                    : Vec4<T>::zero();
+                    ? *reinterpret_cast<const typename Vec4io<T>::raw*>((const T*)p.aux + obase + (size_t)m * p.ldo + ncol)
+                    : Vec4io<T>::zero();
             }
     }
 
@@ -468,7 +448,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
                 float v[4] = {q.x, q.y, q.z, q.w};
                 const int m = mrow0 + it * RPI;
                 if (m < m_lim && ncol < p.N)
-                    epilogue4<T, EPI, ACT>(p, obase + (size_t)m * p.ldo + ncol, v, Vec4<T>::zero());
+                    epilogue4<T, EPI, ACT>(p, obase + (size_t)m * p.ldo + ncol, v, Vec4io<T>::zero());
             }
         } else {
 #pragma unroll

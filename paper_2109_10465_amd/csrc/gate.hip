@@ -5,65 +5,87 @@
 
 // ---------------------------------------------------------------------------
 // logits[T,E] = x[T,d] * Wg[d,E] (+ bias)
-// Workgroup: 64 tokens x all experts; thread (ty,tx) owns 4 tokens x NE
-// consecutive experts; x and Wg are staged through LDS in slabs of DK columns.
+// Workgroup: 64 tokens; experts in passes of 32.  Thread (ty,tx) owns a 2-token
+// x 4-expert register tile, so one 8-byte and one 16-byte LDS read feed 8 FMAs.
+// x is staged transposed ([k][token]) and Wg as is ([k][expert]) in slabs of
+// GL_DK reduction entries; every output is one sequential fp32 FMA chain.
 // ---------------------------------------------------------------------------
 #define GL_TB 64
-#define GL_DK 32
+#define GL_DK 64
 
-template <typename T, int NE>
+template <typename T>
 __global__ __launch_bounds__(256) void gate_logits_kernel(
     int Tn, int d, int E, const T* __restrict__ x, const float* __restrict__ Wg,
     const float* __restrict__ bias, float* __restrict__ logits) {
-    constexpr int EP = 16 * NE;
-    __shared__ float xs[GL_TB][GL_DK + 1];
-    __shared__ float ws[GL_DK][EP];
-    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    __shared__ float xs[GL_DK][GL_TB + 4];
+    __shared__ __align__(16) float ws[GL_DK][32];
+    const int tid = threadIdx.x, ty = tid >> 3, tx = tid & 7;
     const int t0 = blockIdx.x * GL_TB;
-    float acc[4][NE];
+    constexpr int CN = Chunk<T>::N;
+    constexpr int CPR = GL_DK / CN;  // 16-byte chunks per token row of the slab
+    constexpr int XPT = GL_TB * CPR / 256;   // x chunks per thread per slab
+    constexpr int WPT = GL_DK * 32 / 256;    // Wg entries per thread per slab
+    static_assert(GL_TB * CPR % 256 == 0, "slab must divide over the workgroup");
+    for (int e0 = 0; e0 < E; e0 += 32) {
+        float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        float xr[XPT][CN], wr[WPT];
+        // slab k0 -> registers (zero outside the tensors)
+        auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+            for (int j = 0; j < XPT; ++j) {
+                const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
 #pragma unroll
-        for (int a = 0; a < NE; ++a) acc[i][a] = 0.0f;
-    constexpr int CN = Chunk<T>::N;           // elements per 16-byte chunk
-    constexpr int CPR = GL_DK / CN;           // chunks per token row of the slab
-    for (int k0 = 0; k0 < d; k0 += GL_DK) {
-        for (int c = tid; c < GL_TB * CPR; c += 256) {
-            const int r = c / CPR, cc = c - r * CPR;
-            float v[CN];
+                for (int i = 0; i < CN; ++i) xr[j][i] = 0.0f;
+                if (t0 + r < Tn && k0 + cc * CN < d) Chunk<T>::load(x + (size_t)(t0 + r) * d + k0 + cc * CN, xr[j]);
+            }
 #pragma unroll
-            for (int i = 0; i < CN; ++i) v[i] = 0.0f;
-            if (t0 + r < Tn && k0 + cc * CN < d) Chunk<T>::load(x + (size_t)(t0 + r) * d + k0 + cc * CN, v);
+            for (int j = 0; j < WPT; ++j) {
+                const int c = tid + j * 256, r = c >> 5, e = c & 31;
+                wr[j] = (k0 + r < d && e0 + e < E) ? Wg[(size_t)(k0 + r) * E + e0 + e] : 0.0f;
+            }
+        };
+        fetch(0);
+        for (int k0 = 0; k0 < d; k0 += GL_DK) {
+            __syncthreads();
 #pragma unroll
-            for (int i = 0; i < CN; ++i) xs[r][cc * CN + i] = v[i];
-        }
-        for (int c = tid; c < GL_DK * EP; c += 256) {
-            const int r = c / EP, e = c - r * EP;
-            ws[r][e] = (k0 + r < d && e < E) ? Wg[(size_t)(k0 + r) * E + e] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll 4
-        for (int kk = 0; kk < GL_DK; ++kk) {
-            float w[NE];
+            for (int j = 0; j < XPT; ++j) {
+                const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
 #pragma unroll
-            for (int a = 0; a < NE; ++a) w[a] = ws[kk][tx * NE + a];
+                for (int i = 0; i < CN; ++i) xs[cc * CN + i][r] = xr[j][i];
+            }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float xv = xs[ty * 4 + i][kk];
+            for (int j = 0; j < WPT; ++j) {
+                const int c = tid + j * 256;
+                ws[c >> 5][c & 31] = wr[j];
+            }
+            __syncthreads();
+            if (k0 + GL_DK < d) fetch(k0 + GL_DK);   // next slab travels while this one is used
+            for (int kb = 0; kb < GL_DK; kb += 8) {   // 16 LDS reads in flight, then 64 FMAs
+                float2 xv[8];
+                float4 wv[8];
 #pragma unroll
-                for (int a = 0; a < NE; ++a) acc[i][a] = fmaf(xv, w[a], acc[i][a]);
+                for (int u = 0; u < 8; ++u) {
+                    xv[u] = *reinterpret_cast<const float2*>(&xs[kb + u][ty * 2]);
+                    wv[u] = *reinterpret_cast<const float4*>(&ws[kb + u][tx * 4]);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    acc[0][0] = fmaf(xv[u].x, wv[u].x, acc[0][0]); acc[0][1] = fmaf(xv[u].x, wv[u].y, acc[0][1]);
+                    acc[0][2] = fmaf(xv[u].x, wv[u].z, acc[0][2]); acc[0][3] = fmaf(xv[u].x, wv[u].w, acc[0][3]);
+                    acc[1][0] = fmaf(xv[u].y, wv[u].x, acc[1][0]); acc[1][1] = fmaf(xv[u].y, wv[u].y, acc[1][1]);
+                    acc[1][2] = fmaf(xv[u].y, wv[u].z, acc[1][2]); acc[1][3] = fmaf(xv[u].y, wv[u].w, acc[1][3]);
+                }
             }
         }
-        __syncthreads();
-    }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int t = t0 + ty * 4 + i;
-        if (t >= Tn) continue;
+        for (int i = 0; i < 2; ++i) {
+            const int t = t0 + ty * 2 + i;
+            if (t >= Tn) continue;
 #pragma unroll
-        for (int a = 0; a < NE; ++a) {
-            const int e = tx * NE + a;
-            if (e < E) logits[(size_t)t * E + e] = acc[i][a] + (bias ? bias[e] : 0.0f);
+            for (int a = 0; a < 4; ++a) {
+                const int e = e0 + tx * 4 + a;
+                if (e < E) logits[(size_t)t * E + e] = acc[i][a] + (bias ? bias[e] : 0.0f);
+            }
         }
     }
 }
@@ -71,11 +93,8 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(
 template <typename T>
 static void launch_gate_logits(const moe_shape* s, const void* x, const float* Wg, const float* bias,
                                float* logits, hipStream_t st) {
-    const int grid = ceil_div(s->T, GL_TB);
-    const int ne = ceil_div(s->E, 16);
-#define GL(NE) gate_logits_kernel<T, NE><<<grid, 256, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits)
-    if (ne <= 1) GL(1); else if (ne <= 2) GL(2); else if (ne <= 4) GL(4); else if (ne <= 8) GL(8); else GL(16);
-#undef GL
+    gate_logits_kernel<T><<<ceil_div(s->T, GL_TB), 256, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg,
+                                                                  bias, logits);
 }
 
 extern "C" int moe_gate_logits(const moe_shape* shape, const void* x, const float* Wg,
@@ -136,7 +155,7 @@ extern "C" int moe_gate_bwd(const moe_shape* shape, const float* dgate_w, const 
 // dWg[d,E] = x^T dlogits : partial sums over token chunks, then an ordered sum
 // ---------------------------------------------------------------------------
 #define GW_DT 64   // d columns per workgroup
-#define GW_TT 32   // tokens per LDS slab
+#define GW_TT 64   // tokens per LDS slab
 
 static inline int gw_chunks(const moe_shape* s) {
     // enough workgroups to fill the chip, at least 256 tokens per chunk
@@ -149,49 +168,83 @@ size_t gate_logits_bwd_ws_bytes(const moe_shape* s) {
     return align_up((size_t)gw_chunks(s) * s->d_model * s->E * 4, 256);
 }
 
-template <typename T, int NE>  // thread owns experts eg*NE .. eg*NE+NE-1, eg = tid/64
+// Workgroup: 64 columns of d x one chunk of tokens; experts in passes of 32.
+// Thread (ti,te) owns a 4-column x 2-expert register tile.
+template <typename T>
 __global__ __launch_bounds__(256) void gate_dwg_partial_kernel(
     int Tn, int d, int E, int tok_per_chunk, const T* __restrict__ x,
     const float* __restrict__ dlogits, float* __restrict__ partial) {
-    constexpr int EP = 4 * NE;
-    __shared__ float xs[GW_TT][GW_DT];
-    __shared__ float dls[GW_TT][EP];
-    const int tid = threadIdx.x, i = tid & 63, eg = tid >> 6;
+    __shared__ __align__(16) float xs[GW_TT][GW_DT];
+    __shared__ __align__(16) float dls[GW_TT][32];
+    const int tid = threadIdx.x, ti = tid & 15, te = tid >> 4;
     const int i0 = blockIdx.x * GW_DT;
     const int tbeg = blockIdx.y * tok_per_chunk;
     const int tend = min(Tn, tbeg + tok_per_chunk);
-    float acc[NE];
-#pragma unroll
-    for (int a = 0; a < NE; ++a) acc[a] = 0.0f;
     constexpr int CN = Chunk<T>::N, CPR = GW_DT / CN;
-    for (int ts = tbeg; ts < tend; ts += GW_TT) {
-        for (int c = tid; c < GW_TT * CPR; c += 256) {
-            const int r = c / CPR, cc = c - r * CPR;
-            float v[CN];
+    constexpr int XPT = GW_TT * CPR / 256 > 0 ? GW_TT * CPR / 256 : 1;
+    constexpr int DPT = GW_TT * 32 / 256;
+    for (int e0 = 0; e0 < E; e0 += 32) {
+        float acc[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
+        float xr[XPT][CN], dr[DPT];
+        auto fetch = [&](int ts) {
 #pragma unroll
-            for (int q = 0; q < CN; ++q) v[q] = 0.0f;
-            if (ts + r < tend && i0 + cc * CN < d) Chunk<T>::load(x + (size_t)(ts + r) * d + i0 + cc * CN, v);
+            for (int j = 0; j < XPT; ++j) {
+                const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
 #pragma unroll
-            for (int q = 0; q < CN; ++q) xs[r][cc * CN + q] = v[q];
+                for (int q = 0; q < CN; ++q) xr[j][q] = 0.0f;
+                if (c < GW_TT * CPR && ts + r < tend && i0 + cc * CN < d)
+                    Chunk<T>::load(x + (size_t)(ts + r) * d + i0 + cc * CN, xr[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < DPT; ++j) {
+                const int c = tid + j * 256, r = c >> 5, e = c & 31;
+                dr[j] = (ts + r < tend && e0 + e < E) ? dlogits[(size_t)(ts + r) * E + e0 + e] : 0.0f;
+            }
+        };
+        fetch(tbeg);
+        for (int ts = tbeg; ts < tend; ts += GW_TT) {
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < XPT; ++j) {
+                const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
+                if (c < GW_TT * CPR) {
+#pragma unroll
+                    for (int q = 0; q < CN; ++q) xs[r][cc * CN + q] = xr[j][q];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < DPT; ++j) {
+                const int c = tid + j * 256;
+                dls[c >> 5][c & 31] = dr[j];
+            }
+            __syncthreads();
+            if (ts + GW_TT < tend) fetch(ts + GW_TT);
+            for (int tb = 0; tb < GW_TT; tb += 8) {   // 16 LDS reads in flight, then 64 FMAs
+                float4 xv[8];
+                float2 dv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    xv[u] = *reinterpret_cast<const float4*>(&xs[tb + u][ti * 4]);
+                    dv[u] = *reinterpret_cast<const float2*>(&dls[tb + u][te * 2]);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    acc[0][0] = fmaf(xv[u].x, dv[u].x, acc[0][0]); acc[0][1] = fmaf(xv[u].x, dv[u].y, acc[0][1]);
+                    acc[1][0] = fmaf(xv[u].y, dv[u].x, acc[1][0]); acc[1][1] = fmaf(xv[u].y, dv[u].y, acc[1][1]);
+                    acc[2][0] = fmaf(xv[u].z, dv[u].x, acc[2][0]); acc[2][1] = fmaf(xv[u].z, dv[u].y, acc[2][1]);
+                    acc[3][0] = fmaf(xv[u].w, dv[u].x, acc[3][0]); acc[3][1] = fmaf(xv[u].w, dv[u].y, acc[3][1]);
+                }
+            }
         }
-        for (int c = tid; c < GW_TT * EP; c += 256) {
-            const int r = c / EP, e = c - r * EP;
-            dls[r][e] = (ts + r < tend && e < E) ? dlogits[(size_t)(ts + r) * E + e] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll 4
-        for (int tt = 0; tt < GW_TT; ++tt) {
-            const float xv = xs[tt][i];
 #pragma unroll
-            for (int a = 0; a < NE; ++a) acc[a] = fmaf(xv, dls[tt][eg * NE + a], acc[a]);
-        }
-        __syncthreads();
-    }
-    if (i0 + i < d) {
-        float* out = partial + ((size_t)blockIdx.y * d + i0 + i) * E;
+        for (int a = 0; a < 4; ++a) {
+            const int i = i0 + ti * 4 + a;
+            if (i >= d) continue;
+            float* out = partial + ((size_t)blockIdx.y * d + i) * E;
 #pragma unroll
-        for (int a = 0; a < NE; ++a)
-            if (eg * NE + a < E) out[eg * NE + a] = acc[a];
+            for (int b = 0; b < 2; ++b)
+                if (e0 + te * 2 + b < E) out[e0 + te * 2 + b] = acc[a][b];
+        }
     }
 }
 
@@ -207,50 +260,101 @@ __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(int n, int nchunk,
 
 // ---------------------------------------------------------------------------
 // dx[t,:] += dlogits[t,:] * Wg^T
-// Workgroup: 32 tokens; loops over 64-column slabs of d; thread (i, tg) owns
-// column i of the slab for 8 tokens.
+// Workgroup: 64 tokens, loops over 64-column slabs of d; thread (ty,tx) owns a
+// 4-token x 4-column register tile; dlogits and Wg are staged transposed
+// ([expert][token], [expert][column]) so both operands are 16-byte LDS reads.
 // ---------------------------------------------------------------------------
-#define GX_TB 32
+#define GX_TB 64
 
 template <typename T>
 __global__ __launch_bounds__(256) void gate_dx_kernel(int Tn, int d, int E,
                                                       const float* __restrict__ dlogits,
                                                       const float* __restrict__ Wg,
                                                       T* __restrict__ dx) {
-    extern __shared__ float smem[];
-    float* dls = smem;                 // [GX_TB][E]
-    float* wgs = smem + GX_TB * E;     // [64 columns][64 experts + 1]
-    const int tid = threadIdx.x, i = tid & 63, tg = tid >> 6;
+    extern __shared__ __align__(16) float smem[];
+    float* dls = smem;                     // [E][GX_TB + 4]
+    float* wgs = smem + E * (GX_TB + 4);   // [min(E,64)][64 + 4]
+    constexpr int LD = GX_TB + 4;
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
     const int t0 = blockIdx.x * GX_TB;
     for (int c = tid; c < GX_TB * E; c += 256) {
-        const int r = c / E;
-        dls[c] = t0 + r < Tn ? dlogits[(size_t)t0 * E + c] : 0.0f;
+        const int r = c / E, e = c - r * E;
+        dls[e * LD + r] = t0 + r < Tn ? dlogits[(size_t)t0 * E + c] : 0.0f;
     }
-    for (int i0 = 0; i0 < d; i0 += 64) {
-        float acc[8];
+    // E <= 64: the Wg slab of the next 64 columns is prefetched into registers and
+    // the dx values to be updated are requested before the FMA loop, so neither
+    // latency is exposed; E > 64 falls back to slab-by-slab staging.
+    typedef typename Vec4io<T>::raw raw;
+    constexpr int WPT = 64 * 64 / 256;
+    float wr[WPT];
+    auto fetch_w = [&](int i0, int e0, int ne) {
 #pragma unroll
-        for (int a = 0; a < 8; ++a) acc[a] = 0.0f;
+        for (int j = 0; j < WPT; ++j) {
+            const int c = tid + j * 256;
+            const int r = c / ne, e = c - r * ne;
+            wr[j] = (c < 64 * ne && i0 + r < d) ? Wg[(size_t)(i0 + r) * E + e0 + e] : 0.0f;
+        }
+    };
+    auto commit_w = [&](int ne) {
+#pragma unroll
+        for (int j = 0; j < WPT; ++j) {
+            const int c = tid + j * 256;
+            const int r = c / ne, e = c - r * ne;
+            if (c < 64 * ne) wgs[e * LD + r] = wr[j];
+        }
+    };
+    const bool single = E <= 64;
+    if (single) fetch_w(0, 0, E);
+    for (int i0 = 0; i0 < d; i0 += 64) {
+        float acc[4][4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[a][b] = 0.0f;
+        const int i = i0 + tx * 4;
+        raw cur_raw[4];
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const int t = t0 + ty * 4 + a;
+            cur_raw[a] = (i < d && t < Tn) ? *reinterpret_cast<const raw*>(dx + (size_t)t * d + i) : Vec4io<T>::zero();
+        }
         for (int e0 = 0; e0 < E; e0 += 64) {
             const int ne = min(64, E - e0);
+            if (!single) fetch_w(i0, e0, ne);
             __syncthreads();
-            for (int c = tid; c < 64 * ne; c += 256) {
-                const int r = c / ne, e = c - r * ne;
-                wgs[r * 65 + e] = i0 + r < d ? Wg[(size_t)(i0 + r) * E + e0 + e] : 0.0f;
-            }
+            commit_w(ne);
             __syncthreads();
-            for (int e = 0; e < ne; ++e) {
-                const float w = wgs[i * 65 + e];
+            if (single && i0 + 64 < d) fetch_w(i0 + 64, 0, E);
+            for (int eb = 0; eb < ne; eb += 4) {   // 8 LDS reads in flight, then 64 FMAs
+                float4 dv[4], wv[4];
 #pragma unroll
-                for (int a = 0; a < 8; ++a) acc[a] = fmaf(dls[(tg * 8 + a) * E + e0 + e], w, acc[a]);
+                for (int u = 0; u < 4; ++u) {
+                    const int e = min(eb + u, ne - 1);
+                    dv[u] = *reinterpret_cast<const float4*>(dls + (e0 + e) * LD + ty * 4);
+                    wv[u] = *reinterpret_cast<const float4*>(wgs + e * LD + tx * 4);
+                    if (eb + u >= ne) wv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float dd[4] = {dv[u].x, dv[u].y, dv[u].z, dv[u].w};
+                    const float ww[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
+#pragma unroll
+                    for (int a = 0; a < 4; ++a)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) acc[a][b] = fmaf(dd[a], ww[b], acc[a][b]);
+                }
             }
         }
-        if (i0 + i < d) {
+        if (i < d) {
 #pragma unroll
-            for (int a = 0; a < 8; ++a) {
-                const int t = t0 + tg * 8 + a;
+            for (int a = 0; a < 4; ++a) {
+                const int t = t0 + ty * 4 + a;
                 if (t < Tn) {
-                    T* p = dx + (size_t)t * d + i0 + i;
-                    st_f32<T>(p, ld_f32<T>(p) + acc[a]);
+                    float cur[4];
+                    Vec4io<T>::unpack(cur_raw[a], cur);
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) cur[b] += acc[a][b];
+                    *reinterpret_cast<raw*>(dx + (size_t)t * d + i) = Vec4io<T>::pack(cur);
                 }
             }
         }
@@ -265,15 +369,16 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
     const int tpc = ceil_div(ceil_div(s->T, nch), GW_TT) * GW_TT;
     const int nch_used = ceil_div(s->T, tpc);
     dim3 grid(ceil_div(s->d_model, GW_DT), nch_used);
-    const int ne = ceil_div(s->E, 4);
-#define GW(NE) gate_dwg_partial_kernel<T, NE><<<grid, 256, 0, st>>>(s->T, s->d_model, s->E, tpc, (const T*)x, dlogits, partial)
-    if (ne <= 1) GW(1); else if (ne <= 2) GW(2); else if (ne <= 4) GW(4); else if (ne <= 8) GW(8);
-    else if (ne <= 16) GW(16); else if (ne <= 32) GW(32); else GW(64);
-#undef GW
+    gate_dwg_partial_kernel<T><<<grid, 256, 0, st>>>(s->T, s->d_model, s->E, tpc, (const T*)x, dlogits, partial);
     const int n = s->d_model * s->E;
     gate_dwg_reduce_kernel<<<ceil_div(n, 256), 256, 0, st>>>(n, nch_used, partial, dWg);
     if (dx) {
-        const size_t smem = ((size_t)GX_TB * s->E + 64 * 65) * 4;
+        const size_t smem = ((size_t)s->E + (s->E < 64 ? s->E : 64)) * (GX_TB + 4) * 4;
+        if (smem > 64 * 1024) {   // opt in to more than 64 KB of LDS (E > 128)
+            static const hipError_t attr = hipFuncSetAttribute(
+                (const void*)gate_dx_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+            (void)attr;
+        }
         gate_dx_kernel<T><<<ceil_div(s->T, GX_TB), 256, smem, st>>>(s->T, s->d_model, s->E, dlogits, Wg, (T*)dx);
     }
 }

@@ -66,6 +66,26 @@ template <> struct Chunk<bf16_t> {
     }
 };
 
+// 4 consecutive elements of one row as the activation type (8 or 16 bytes)
+template <typename T> struct Vec4io;
+template <> struct Vec4io<float> {
+    typedef float4 raw;
+    __device__ static __forceinline__ raw zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ static __forceinline__ raw pack(const float (&v)[4]) { return make_float4(v[0], v[1], v[2], v[3]); }
+    __device__ static __forceinline__ void unpack(raw q, float (&v)[4]) { v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w; }
+};
+template <> struct Vec4io<bf16_t> {
+    typedef uint2 raw;
+    __device__ static __forceinline__ raw zero() { return make_uint2(0u, 0u); }
+    __device__ static __forceinline__ raw pack(const float (&v)[4]) {
+        return make_uint2(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
+    }
+    __device__ static __forceinline__ void unpack(raw q, float (&v)[4]) {
+        v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xffff0000u);
+        v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xffff0000u);
+    }
+};
+
 // ---- wave64 reductions (butterfly: every lane ends with the same bits) ------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -1,25 +1,27 @@
 // moe_gate_route: softmax / top-k gate and the capacity assignment with
 // Random-Token-Selection priority (Sec. 5.1 "MoE setting", Sec. 3.1).
 //
-// Four kernels on one stream, all integer-exact and free of float atomics:
-//   1. gate_topk     one wave per token: softmax, top-k, gate weights; per
-//                    64-token chunk a histogram of (expert, choice) segments.
-//   2. route_scan    one workgroup: exclusive prefix of the histograms over
-//                    chunks, segment offsets, expert_demand / expert_count.
-//   3. route_place   stable counting-sort placement: every candidate (t,j) is
-//                    written into its (expert, choice) segment in token order.
-//   4. route_rank    rank inside a segment by counting the candidates that
+// Three kernels on one stream, all integer-exact and free of float atomics:
+//   1. gate_topk     one thread per token: top-k, softmax, gate weights; per
+//                    256-token chunk a histogram of (expert, choice) segments.
+//   2. route_place   every workgroup re-derives, from the chunk histograms, the
+//                    segment offsets and its own chunk's prefix (a few KB of L2
+//                    reads instead of a separate scan launch), then writes its
+//                    candidates (t,j) into their (expert, choice) segments in
+//                    token order: a stable counting sort.  Workgroup 0 also
+//                    publishes segment offsets, expert_demand and expert_count.
+//   3. route_rank    rank inside a segment by counting the candidates that
 //                    precede it in (key descending, token ascending) order,
 //                    LDS-tiled; slot = rank (+ first-choice demand for j = 1).
-// Total work is O(T*E + sum over segments n^2 / 1), bounded by the single-expert
-// worst case; typical balanced routing makes step 4 a few microseconds.
+// Work is O(T*E + sum over segments of n^2), bounded by the single-expert worst
+// case; balanced routing makes step 3 a few microseconds.
 #include "moe_common.h"
 
-#define CHUNK 64        // tokens per histogram chunk (= per gate_topk workgroup)
+#define CHUNK 256       // tokens per histogram chunk (= per gate_topk / route_place workgroup)
 #define RANK_TILE 256   // candidates per route_rank workgroup
 
 struct RouteWs {
-    int32_t* hist;        // [nchunk][k*E] -> exclusive prefix over chunks
+    int32_t* hist;        // [nchunk][k*E] candidates per chunk and segment
     int32_t* seg_start;   // [k*E+1] segment seg = e*k+j starts here in seg_tok/seg_key
     int32_t* tile_start;  // [k*E+1] prefix of ceil(n_seg / RANK_TILE)
     int32_t* seg_tok;     // [T*k]
@@ -47,105 +49,112 @@ static RouteWs carve(const moe_shape* s, void* ws) {
 }
 
 // ---------------------------------------------------------------------------
-// 1. gate: softmax, top-k (largest logits, ties -> smaller id), gate weights
+// 1. gate: top-k (largest logits, ties -> smaller id), softmax, gate weights
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void argmax_reduce(float& v, int& i) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const float ov = __shfl_xor(v, o, MOE_WAVE);
-        const int oi = __shfl_xor(i, o, MOE_WAVE);
-        if (ov > v || (ov == v && oi < i)) { v = ov; i = oi; }
-    }
+// (value, expert) pairs ordered by value descending, expert id ascending
+__device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
+    return va > vb || (va == vb && ia < ib);
 }
 
-template <int NI>  // experts per lane: E <= 64*NI
-__global__ __launch_bounds__(256) void gate_topk_kernel(
+// LPT lanes share one token, 4 consecutive experts per lane (4*LPT >= E), so a
+// token's logits are read with one coalesced 16-byte load per lane and reduced
+// with log2(LPT) butterfly steps; a workgroup walks its 256-token chunk in LPT
+// rounds of 256/LPT tokens.
+template <int LPT>
+__global__ __launch_bounds__(CHUNK) void gate_topk_kernel(
     int T, int E, int k, const float* __restrict__ logits, float* __restrict__ probs,
     int32_t* __restrict__ expert_idx, float* __restrict__ gate_w, int32_t* __restrict__ hist) {
     __shared__ int32_t s_hist[512];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int kE = k * E;
-    for (int i = threadIdx.x; i < kE; i += 256) s_hist[i] = 0;
+    for (int i = threadIdx.x; i < kE; i += CHUNK) s_hist[i] = 0;
     __syncthreads();
-    const int t0 = blockIdx.x * CHUNK + wave * (CHUNK / 4);
-    for (int tt = 0; tt < CHUNK / 4; ++tt) {
-        const int t = t0 + tt;
-        if (t >= T) break;  // uniform per wave
-        float l[NI];
+    constexpr int TPI = CHUNK / LPT;  // tokens per round
+    const int gl = threadIdx.x % LPT, slot = threadIdx.x / LPT;
+    const int e4 = gl * 4;
+    const bool vec = (E & 3) == 0;
+    for (int it = 0; it < LPT; ++it) {
+        const int t = blockIdx.x * CHUNK + it * TPI + slot;
+        const bool valid = t < T;   // uniform within a token's lane group
+        float l[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (valid) {
+            const float* row = logits + (size_t)t * E;
+            if (vec) {
+                if (e4 < E) {
+                    const float4 q = *reinterpret_cast<const float4*>(row + e4);
+                    l[0] = q.x; l[1] = q.y; l[2] = q.z; l[3] = q.w;
+                }
+            } else {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int e = lane + 64 * i;
-            l[i] = e < E ? logits[(size_t)t * E + e] : -INFINITY;
-        }
-        // first choice
-        float bv = -INFINITY;
-        int bi = 0x7fffffff;
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-            if (lane + 64 * i < E && (l[i] > bv || bi == 0x7fffffff)) { bv = l[i]; bi = lane + 64 * i; }
-        argmax_reduce(bv, bi);
-        const int e0 = bi;
-        const float mx = bv;
-        // second choice: same reduction with e0 masked out
-        int e1 = -1;
-        if (k == 2) {
-            float cv = -INFINITY;
-            int ci = 0x7fffffff;
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                const int e = lane + 64 * i;
-                if (e < E && e != e0 && (l[i] > cv || ci == 0x7fffffff)) { cv = l[i]; ci = e; }
+                for (int i = 0; i < 4; ++i)
+                    if (e4 + i < E) l[i] = row[e4 + i];
             }
-            argmax_reduce(cv, ci);
-            e1 = ci;
         }
-        // softmax
-        float ex[NI], part = 0.0f;
+        // the lane's own best two (ascending ids, strict comparisons)
+        float v0 = -INFINITY, v1 = -INFINITY;
+        int i0 = 0x7fffffff, i1 = 0x7fffffff;
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            ex[i] = lane + 64 * i < E ? expf(l[i] - mx) : 0.0f;
+        for (int i = 0; i < 4; ++i) {
+            const int e = e4 + i;
+            if (e < E) {
+                if (better(l[i], e, v0, i0)) { v1 = v0; i1 = i0; v0 = l[i]; i0 = e; }
+                else if (better(l[i], e, v1, i1)) { v1 = l[i]; i1 = e; }
+            }
+        }
+#pragma unroll
+        for (int o = LPT / 2; o > 0; o >>= 1) {
+            const float w0 = __shfl_xor(v0, o, MOE_WAVE), w1 = __shfl_xor(v1, o, MOE_WAVE);
+            const int j0 = __shfl_xor(i0, o, MOE_WAVE), j1 = __shfl_xor(i1, o, MOE_WAVE);
+            if (better(w0, j0, v0, i0)) {
+                if (better(v0, i0, w1, j1)) { v1 = v0; i1 = i0; } else { v1 = w1; i1 = j1; }
+                v0 = w0; i0 = j0;
+            } else if (better(w0, j0, v1, i1)) {
+                v1 = w0; i1 = j0;
+            }
+        }
+        float ex[4], part = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            ex[i] = (valid && e4 + i < E) ? expf(l[i] - v0) : 0.0f;
             part += ex[i];
         }
-        const float sum = wave_sum(part);
-        float p[NI];
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            p[i] = ex[i] / sum;
-            if (lane + 64 * i < E) probs[(size_t)t * E + lane + 64 * i] = p[i];
-        }
-        // probabilities of the chosen experts, broadcast from their owner lanes
-        float p0 = 0.0f, p1 = 0.0f;
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const float a = __shfl(p[i], e0 & 63, MOE_WAVE);
-            if ((e0 >> 6) == i) p0 = a;
-            if (k == 2) {
-                const float b = __shfl(p[i], e1 & 63, MOE_WAVE);
-                if ((e1 >> 6) == i) p1 = b;
-            }
-        }
-        if (lane == 0) {
-            if (k == 1) {
-                expert_idx[t] = e0;
-                gate_w[t] = p0;
-                atomicAdd(&s_hist[e0], 1);
+        for (int o = LPT / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, MOE_WAVE);
+        const float sum = part;
+        if (valid) {
+            float* pr = probs + (size_t)t * E;
+            if (vec) {
+                if (e4 < E)
+                    *reinterpret_cast<float4*>(pr + e4) = make_float4(ex[0] / sum, ex[1] / sum, ex[2] / sum, ex[3] / sum);
             } else {
-                const float S = p0 + p1;
-                expert_idx[2 * t] = e0;
-                expert_idx[2 * t + 1] = e1;
-                gate_w[2 * t] = p0 / S;
-                gate_w[2 * t + 1] = p1 / S;
-                atomicAdd(&s_hist[e0 * 2], 1);
-                atomicAdd(&s_hist[e1 * 2 + 1], 1);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (e4 + i < E) pr[e4 + i] = ex[i] / sum;
+            }
+            if (gl == 0) {
+                const float p0 = 1.0f / sum;   // = exp(0) / sum
+                if (k == 1) {
+                    expert_idx[t] = i0;
+                    gate_w[t] = p0;
+                    atomicAdd(&s_hist[i0], 1);
+                } else {
+                    const float p1 = expf(v1 - v0) / sum;
+                    const float S = p0 + p1;
+                    expert_idx[2 * t] = i0;
+                    expert_idx[2 * t + 1] = i1;
+                    gate_w[2 * t] = p0 / S;
+                    gate_w[2 * t + 1] = p1 / S;
+                    atomicAdd(&s_hist[i0 * 2], 1);
+                    atomicAdd(&s_hist[i1 * 2 + 1], 1);
+                }
             }
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kE; i += 256) hist[(size_t)blockIdx.x * kE + i] = s_hist[i];
+    for (int i = threadIdx.x; i < kE; i += CHUNK) hist[(size_t)blockIdx.x * kE + i] = s_hist[i];
 }
 
 // ---------------------------------------------------------------------------
-// 2. scan over chunks per segment, then over segments
+// 2. segment offsets + stable placement of candidates (token order kept)
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 #pragma unroll
@@ -156,79 +165,97 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
     return v;
 }
 
-__global__ __launch_bounds__(1024) void route_scan_kernel(
-    int E, int k, int C, int nchunk, int32_t* __restrict__ hist, int32_t* __restrict__ seg_start,
-    int32_t* __restrict__ tile_start, int32_t* __restrict__ expert_count,
-    int32_t* __restrict__ expert_demand) {
-    __shared__ int32_t s_total[512];
+__global__ __launch_bounds__(CHUNK) void route_place_kernel(
+    int T, int E, int k, int C, int nchunk, const int32_t* __restrict__ expert_idx,
+    const float* __restrict__ keys, const int32_t* __restrict__ hist,
+    int32_t* __restrict__ seg_start, int32_t* __restrict__ tile_start,
+    int32_t* __restrict__ expert_count, int32_t* __restrict__ expert_demand,
+    int32_t* __restrict__ seg_tok, float* __restrict__ seg_key) {
+    __shared__ int32_t s_tot[512];          // candidates per segment, whole batch
+    __shared__ int32_t s_base[512];         // segment start + candidates in earlier chunks
+    __shared__ int32_t s_wcnt[CHUNK / 64][512];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int chunk = blockIdx.x;
     const int kE = k * E;
-    for (int seg = wave; seg < kE; seg += 16) {
-        int running = 0;
-        for (int c0 = 0; c0 < nchunk; c0 += 64) {
-            const int c = c0 + lane;
-            const int v = c < nchunk ? hist[(size_t)c * kE + seg] : 0;
-            const int incl = wave_incl_scan(v, lane);
-            if (c < nchunk) hist[(size_t)c * kE + seg] = running + incl - v;
-            running += __shfl(incl, 63, MOE_WAVE);
+    for (int seg = threadIdx.x; seg < kE; seg += CHUNK) {
+        int tot = 0, pre = 0;
+        int c = 0;
+        for (; c + 8 <= nchunk; c += 8) {   // 8 independent loads in flight
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = hist[(size_t)(c + u) * kE + seg];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                pre += c + u < chunk ? v[u] : 0;
+                tot += v[u];
+            }
         }
-        if (lane == 0) s_total[seg] = running;
+        for (; c < nchunk; ++c) {
+            const int v = hist[(size_t)c * kE + seg];
+            pre += c < chunk ? v : 0;
+            tot += v;
+        }
+        s_tot[seg] = tot;
+        s_base[seg] = pre;
+#pragma unroll
+        for (int w = 0; w < CHUNK / 64; ++w) s_wcnt[w][seg] = 0;
     }
     __syncthreads();
-    if (wave == 0) {
+    if (wave == 0) {  // exclusive scan over segments (seg = e*k+j)
         int run_pos = 0, run_tile = 0;
         for (int s0 = 0; s0 < kE; s0 += 64) {
             const int seg = s0 + lane;
-            const int n = seg < kE ? s_total[seg] : 0;
+            const int n = seg < kE ? s_tot[seg] : 0;
             const int nt = (n + RANK_TILE - 1) / RANK_TILE;
             const int ip = wave_incl_scan(n, lane), it = wave_incl_scan(nt, lane);
             if (seg < kE) {
-                seg_start[seg] = run_pos + ip - n;
-                tile_start[seg] = run_tile + it - nt;
+                const int start = run_pos + ip - n;
+                s_base[seg] += start;
+                if (chunk == 0) {
+                    seg_start[seg] = start;
+                    tile_start[seg] = run_tile + it - nt;
+                }
             }
             run_pos += __shfl(ip, 63, MOE_WAVE);
             run_tile += __shfl(it, 63, MOE_WAVE);
         }
-        if (lane == 0) {
-            seg_start[kE] = run_pos;
-            tile_start[kE] = run_tile;
-        }
-        for (int e = lane; e < E; e += 64) {
-            int dem = s_total[e * k];
-            if (k == 2) dem += s_total[e * k + 1];
-            expert_demand[e] = dem;
-            expert_count[e] = dem < C ? dem : C;
+        if (chunk == 0) {
+            if (lane == 0) {
+                seg_start[kE] = run_pos;
+                tile_start[kE] = run_tile;
+            }
+            for (int e = lane; e < E; e += 64) {
+                int dem = s_tot[e * k];
+                if (k == 2) dem += s_tot[e * k + 1];
+                expert_demand[e] = dem;
+                expert_count[e] = dem < C ? dem : C;
+            }
         }
     }
-}
-
-// ---------------------------------------------------------------------------
-// 3. stable placement of candidates into their segments (token order kept)
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void route_place_kernel(
-    int T, int E, int k, const int32_t* __restrict__ expert_idx, const float* __restrict__ keys,
-    const int32_t* __restrict__ hist, const int32_t* __restrict__ seg_start,
-    int32_t* __restrict__ seg_tok, float* __restrict__ seg_key) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int chunk = blockIdx.x * 4 + wave;
-    const int t = chunk * CHUNK + lane;
+    __syncthreads();
+    const int t = chunk * CHUNK + threadIdx.x;
     const bool valid = t < T;
-    const int kE = k * E;
     const float key = (valid && keys) ? keys[t] : 0.0f;
+    int ev[2] = {-1, -1}, rank[2] = {0, 0};
     for (int j = 0; j < k; ++j) {
         const int e = valid ? expert_idx[(size_t)t * k + j] : -1;
+        ev[j] = e;
         unsigned long long todo = __ballot(valid);
-        int rank = 0;
-        while (todo) {  // one round per distinct expert among the 64 tokens
+        while (todo) {  // one round per distinct expert among the wave's 64 tokens
             const int leader = __ffsll((long long)todo) - 1;
-            const int ev = __shfl(e, leader, MOE_WAVE);
-            const unsigned long long same = __ballot(valid && e == ev);
-            if (valid && e == ev) rank = __popcll(same & ((1ull << lane) - 1ull));
+            const int le = __shfl(e, leader, MOE_WAVE);
+            const unsigned long long same = __ballot(valid && e == le);
+            if (valid && e == le) rank[j] = __popcll(same & ((1ull << lane) - 1ull));
+            if (lane == leader) s_wcnt[wave][le * k + j] = __popcll(same);
             todo &= ~same;
         }
-        if (valid) {
-            const int seg = e * k + j;
-            const int pos = seg_start[seg] + hist[(size_t)chunk * kE + seg] + rank;
+    }
+    __syncthreads();
+    if (valid) {
+        for (int j = 0; j < k; ++j) {
+            const int seg = ev[j] * k + j;
+            int pos = s_base[seg] + rank[j];
+            for (int w = 0; w < wave; ++w) pos += s_wcnt[w][seg];
             seg_tok[pos] = t;
             seg_key[pos] = key;
         }
@@ -236,24 +263,26 @@ __global__ __launch_bounds__(256) void route_place_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// 4. rank inside the segment, slots, slot_src
+// 3. rank inside the segment, slots, slot_src
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(RANK_TILE) void route_rank_kernel(
     int E, int k, int C, int has_keys, const int32_t* __restrict__ seg_start,
     const int32_t* __restrict__ tile_start, const int32_t* __restrict__ seg_tok,
     const float* __restrict__ seg_key, int32_t* __restrict__ slot, int32_t* __restrict__ slot_src) {
     __shared__ float s_key[RANK_TILE];
+    __shared__ int s_seg;
     const int kE = k * E;
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
-    if (b < tile_start[kE]) {
-        // segment owning tile b: the last seg with tile_start[seg] <= b
-        int lo = 0, hi = kE - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (tile_start[mid] <= b) lo = mid; else hi = mid - 1;
-        }
-        const int seg = lo;
+    // segment owning tile b: the one with tile_start[seg] <= b < tile_start[seg+1]
+    // (empty segments have an empty range); found by all threads in parallel
+    if (tid == 0) s_seg = -1;
+    __syncthreads();
+    for (int sg = tid; sg < kE; sg += RANK_TILE)
+        if (tile_start[sg] <= b && b < tile_start[sg + 1]) s_seg = sg;
+    __syncthreads();
+    if (s_seg >= 0) {
+        const int seg = s_seg;
         const int s0 = seg_start[seg], s1 = seg_start[seg + 1];
         const int own0 = s0 + (b - tile_start[seg]) * RANK_TILE;
         const int p = own0 + tid;
@@ -312,14 +341,13 @@ extern "C" int moe_gate_route(const moe_shape* shape, const float* logits,
     const int T = shape->T, E = shape->E, k = shape->k, C = shape->capacity;
     const RouteWs r = carve(shape, ws);
     const int nchunk = n_chunks(shape);
-    const int ni = ceil_div(E, 64);
-#define GATE(NI) gate_topk_kernel<NI><<<nchunk, 256, 0, st>>>(T, E, k, logits, probs, expert_idx, gate_w, r.hist)
-    if (ni == 1) GATE(1); else if (ni == 2) GATE(2); else if (ni == 3) GATE(3); else GATE(4);
+#define GATE(LPT) gate_topk_kernel<LPT><<<nchunk, CHUNK, 0, st>>>(T, E, k, logits, probs, expert_idx, gate_w, r.hist)
+    if (E <= 4) GATE(1); else if (E <= 8) GATE(2); else if (E <= 16) GATE(4); else if (E <= 32) GATE(8);
+    else if (E <= 64) GATE(16); else if (E <= 128) GATE(32); else GATE(64);
 #undef GATE
-    route_scan_kernel<<<1, 1024, 0, st>>>(E, k, C, nchunk, r.hist, r.seg_start, r.tile_start,
-                                          expert_count, expert_demand);
-    route_place_kernel<<<ceil_div(nchunk, 4), 256, 0, st>>>(T, E, k, expert_idx, rts_keys_or_null,
-                                                            r.hist, r.seg_start, r.seg_tok, r.seg_key);
+    route_place_kernel<<<nchunk, CHUNK, 0, st>>>(T, E, k, C, nchunk, expert_idx, rts_keys_or_null, r.hist,
+                                                 r.seg_start, r.tile_start, expert_count, expert_demand,
+                                                 r.seg_tok, r.seg_key);
     const int ntile_max = ceil_div(T * k, RANK_TILE) + k * E;
     route_rank_kernel<<<ntile_max, RANK_TILE, 0, st>>>(E, k, C, rts_keys_or_null != nullptr,
                                                        r.seg_start, r.tile_start, r.seg_tok,
