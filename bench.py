@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-call timings to stderr")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device copy (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1", file=sys.stderr)
@@ -63,6 +65,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+    if args.copy_calibration:
+        # a plain copy kernel of known size: reads 1 GiB, writes 1 GiB
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 3}))
+        return
     B.lib()
     w = I.WORKLOADS[args.workload]
     d = I.make_inputs(w, seed=0)
@@ -121,9 +132,15 @@ def main():
     flops = 12.0 * M * w.d_model * w.d_ff                     # 6 grouped GEMMs, 2*M*d*f each
     peak = PEAK_BF16_MFMA if w.dtype == I.BF16 else PEAK_F32_MFMA
     achieved = flops / (gemm_ms * 1e-3)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"grouped_gemm_{w.name}_hbm_traffic.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            if line.startswith("traffic_bytes_per_launch"):
+                traffic = float(line.split("=")[1])
     roofline = {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step)",
                 "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": None,
+                "frac": achieved / peak, "traffic": traffic,
                 "flops_per_launch": flops / 6.0, "avg_launch_ms": gemm_ms / 6.0,
                 "kept_assignments": M}
 
