@@ -14,9 +14,12 @@
 // either k-contiguous in memory (KC) or r-contiguous (!KC); no transposed copy
 // of any tensor is ever materialised.
 //
-// Structure of a workgroup (4 waves, 2 x 2):
-//   * owns a BM x BN output tile of one expert; workgroup ids are remapped so
-//     that consecutive tiles of one expert land on the same XCD and share its L2;
+// Structure of a workgroup (4 waves, 2 x 2; one persistent workgroup per CU):
+//   * walks BM x BN output tiles; workgroup w serves XCD w % 8 and that XCD's
+//     contiguous run of tiles (= whole experts), so co-resident tiles share
+//     operand panels in the XCD's L2; the slabs of all its tiles form one stream
+//     through the LDS ring, i.e. the next tile's first slabs arrive under the
+//     current tile's epilogue;
 //   * streams BK-deep slabs of both operands with 16-byte buffer loads that
 //     write straight into LDS (no register staging), NSTAGE-1 slabs ahead of
 //     the one being multiplied, so HBM/L2 latency is covered by several slabs
@@ -101,21 +104,7 @@ __device__ __forceinline__ u32x4_t make_desc(const void* p, uint32_t bytes) {
 // serialise every later LDS read behind the load; completion is tracked by
 // hand with vmcnt (see the main loop).
 __device__ __forceinline__ void load_to_lds(u32x4_t desc, uint32_t voff, uint32_t lds_base) {
-#ifndef MOE_DMA_MODE
-#define MOE_DMA_MODE 0
-#endif
-#if MOE_DMA_MODE == 1
-#define MOE_DMA_MODS " nt"
-#elif MOE_DMA_MODE == 2
-#define MOE_DMA_MODS " sc1"
-#elif MOE_DMA_MODE == 3
-#define MOE_DMA_MODS " sc0"
-#elif MOE_DMA_MODE == 4
-#define MOE_DMA_MODS " sc0 sc1"
-#else
-#define MOE_DMA_MODS ""
-#endif
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen" MOE_DMA_MODS " lds"
+    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
 }
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in 15:14)
@@ -276,109 +265,138 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& p, size_t o, float (&v
     }
 }
 
-#ifndef MOE_GEMM_LDS_KB
-#define MOE_GEMM_LDS_KB 144
-#endif
-#define GEMM_LDS_BUDGET (MOE_GEMM_LDS_KB * 1024)  // LDS one workgroup may take (CU: 160 KB)
-
 template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC>
 struct GemmSmem {
     typedef Tile<T, BM, BK, A_KC> TA;
     typedef Tile<T, BN, BK, B_KC> TB;
     static constexpr int STAGE = TA::BYTES + TB::BYTES;
-    // LDS ring: 1 slab being multiplied + NSTAGE-1 in flight
-    static constexpr int NSTAGE = 4 * STAGE <= GEMM_LDS_BUDGET ? 4 : 3 * STAGE <= GEMM_LDS_BUDGET ? 3 : 2;
-    static constexpr int EPI_LD = BN / 2 + 8;  // floats per staged row (4 rows apart -> other bank half)
-    static constexpr size_t OPERANDS = (size_t)NSTAGE * STAGE;
-    static constexpr size_t EPILOGUE = 4 * 32 * (size_t)EPI_LD * sizeof(float);
-    static constexpr size_t BYTES = OPERANDS > EPILOGUE ? OPERANDS : EPILOGUE;
+    static constexpr int NSTAGE = 4;            // LDS ring: 1 slab being multiplied + 3 in flight
+    static constexpr int EPI_LD = BN / 2 + 8;   // floats per staged epilogue row (4 rows apart -> other bank half)
+    static constexpr int EPI_ROWS = 8;          // one accumulator register quad of both lane halves
+    static constexpr size_t RING = (size_t)NSTAGE * STAGE;
+    static constexpr size_t EPILOGUE = 4 * EPI_ROWS * (size_t)EPI_LD * sizeof(float);  // wave-private strips
+    static constexpr size_t BYTES = RING + EPILOGUE;   // the epilogue never touches the ring
     static constexpr int LOADS = TA::PER_THREAD + TB::PER_THREAD;  // per thread per slab
     static_assert((NSTAGE - 1) * LOADS < 64, "vmcnt is a 6-bit counter");
-    static_assert(NSTAGE >= 3, "the loop refills a stage while the next slab is already resident");
     static_assert((BK / Mma<T>::KSTEP) % 2 == 0, "fragment double buffering needs an even number of k-steps");
+    static_assert(BYTES <= 160 * 1024, "LDS of one CU");
 };
 
+// The walk of one workgroup over its tiles.  Workgroup w serves XCD w % 8 (ids
+// are dealt round-robin to the XCDs) and takes every (gridDim/8)-th tile of that
+// XCD's contiguous run of logical tiles (= whole experts), so the ~32 tiles an
+// XCD works on at once share operand panels in its L2.  Tiles beyond an
+// expert's rows are skipped.
+template <int BM, int BN>
+struct TileWalk {
+    int logical, end, step;
+    int e, m0, n0, m_lim, k_lim;   // current tile
+    __device__ __forceinline__ void start(const GemmArgs& p) {
+        const int xcd = blockIdx.x & 7;
+        step = gridDim.x >> 3;
+        logical = xcd * p.tiles_per_xcd + (blockIdx.x >> 3) - step;
+        end = min((xcd + 1) * p.tiles_per_xcd, p.total_tiles);
+    }
+    // moves to the next non-empty tile; false when the walk is over
+    __device__ __forceinline__ bool next(const GemmArgs& p) {
+        const int per_e = p.tiles_m * p.tiles_n;
+        for (;;) {
+            logical += step;
+            if (logical >= end) return false;
+            e = logical / per_e;
+            const int rem = logical - e * per_e;
+            // inside an expert the dimension with fewer tiles varies fastest
+            int tm, tn;
+            if (p.tiles_m <= p.tiles_n) { tn = rem / p.tiles_m; tm = rem - tn * p.tiles_m; }
+            else { tm = rem / p.tiles_n; tn = rem - tm * p.tiles_n; }
+            const int n_e = p.expert_count[e];
+            m0 = tm * BM; n0 = tn * BN;
+            m_lim = p.var_k ? p.M : n_e;
+            k_lim = p.var_k ? n_e : p.K;
+            if (m0 < m_lim) return true;
+        }
+    }
+};
+
+// Persistent workgroups: each walks its tiles and treats the slabs of all of
+// them as one stream through the LDS ring, so the first slabs of the next tile
+// are already resident when the epilogue of the current one ends, and no
+// workgroup launch or cold first load sits between two tiles.
 template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT>
 __global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
     typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC> SM;
     typedef typename SM::TA TA;
     typedef typename SM::TB TB;
+    typedef typename Vec4io<T>::raw raw;
     constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 MFMA tiles per wave (2x2 waves)
     constexpr int KS = BK / Mma<T>::KSTEP;
     constexpr int NS = SM::NSTAGE;
     extern __shared__ __align__(16) unsigned char smem_raw[];
-
-    // XCD-aware tile order: workgroup ids are dealt round-robin to the 8 XCDs, so
-    // give each XCD one contiguous run of logical tiles (= whole experts).
-    const int bid = blockIdx.x;
-#ifdef MOE_DEBUG_NOREMAP
-    const int logical = bid;
-#else
-    const int logical = (bid & 7) * p.tiles_per_xcd + (bid >> 3);
-#endif
-    if (logical >= p.total_tiles) return;
-    const int per_e = p.tiles_m * p.tiles_n;
-    const int e = logical / per_e;
-    const int rem = logical - e * per_e;
-    const int tm = rem / p.tiles_n, tn = rem - tm * p.tiles_n;
-    const int n_e = p.expert_count[e];
-    const int m0 = tm * BM, n0 = tn * BN;
-    const int m_lim = p.var_k ? p.M : n_e;
-    const int k_lim = p.var_k ? n_e : p.K;
-    if (m0 >= m_lim) return;
-
-    const u32x4_t dsA = TA::desc((const T*)p.A + (size_t)e * p.strideA, p.lda, m_lim, k_lim);
-    const u32x4_t dsB = TB::desc((const T*)p.B + (size_t)e * p.strideB, p.ldb, p.N, k_lim);
-    typename TA::Plan planA;
-    typename TB::Plan planB;
-    TA::plan(planA, p.lda, m0, m_lim);
-    TB::plan(planB, p.ldb, n0, p.N);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, g = lane >> 5;
 
-    f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    // epilogue geometry: the wave's (BM/2) x (BN/2) sub-tile goes out in strips of
-    // 32 rows; a lane owns 4 consecutive columns of RPI-strided rows
+    // epilogue geometry: the wave's (BM/2) x (BN/2) sub-tile leaves in strips of 8
+    // rows; a lane owns 4 consecutive columns of RPI-strided rows
     constexpr int ELD = SM::EPI_LD;
     constexpr int WCOLS = BN / 2;
     constexpr int LPR = WCOLS / 4;                // lanes per staged row
     constexpr int RPI = 64 / LPR;                 // rows per wave instruction
-    constexpr int NIT = 32 / RPI;
+    constexpr int NIT = SM::EPI_ROWS / RPI;       // row vectors per lane per strip
+    static_assert(NIT >= 1, "strip narrower than a wavefront");
     const int er = lane / LPR, ec = (lane - er * LPR) * 4;
-    const size_t obase = (size_t)e * p.strideO;
-    const int ncol = n0 + wn * WCOLS + ec;
-    // EPI_MUL: the saved derivative does not depend on the product, so it is
-    // fetched now and rides in registers through the main loop
-    typename Vec4io<T>::raw aux[EPI == EPI_MUL ? TM : 1][EPI == EPI_MUL ? NIT : 1];
-    if constexpr (EPI == EPI_MUL) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const int m = m0 + wm * (BM / 2) + i * 32 + er + it * RPI;
-                aux[i][it] = (m < m_lim && ncol < p.N)
-                    ? *reinterpret_cast<const typename Vec4io<T>::raw*>((const T*)p.aux + obase + (size_t)m * p.ldo + ncol)
-                    : Vec4io<T>::zero();
-            }
-    }
+    float* strip = reinterpret_cast<float*>(smem_raw + SM::RING) + wave * SM::EPI_ROWS * ELD;
 
-    const int nk = (k_lim + BK - 1) / BK;
-    // prologue: slabs 0 .. NS-2 into stages 0 .. NS-2 (slabs past the end read zeros)
+    // ---- producer: the stream of slabs of all tiles of this workgroup ---------
+    TileWalk<BM, BN> pw;           // tile whose slabs are being requested
+    pw.start(p);
+    bool p_more = pw.next(p);
+    int p_kt = 0, p_nk = 0;
+    u32x4_t dsA = {0, 0, 0, 0}, dsB = {0, 0, 0, 0};
+    typename TA::Plan planA;
+    typename TB::Plan planB;
+    auto producer_setup = [&]() {
+        dsA = TA::desc((const T*)p.A + (size_t)pw.e * p.strideA, p.lda, pw.m_lim, pw.k_lim);
+        dsB = TB::desc((const T*)p.B + (size_t)pw.e * p.strideB, p.ldb, p.N, pw.k_lim);
+        TA::plan(planA, p.lda, pw.m0, pw.m_lim);
+        TB::plan(planB, p.ldb, pw.n0, p.N);
+        p_kt = 0;
+        p_nk = (pw.k_lim + BK - 1) / BK;
+    };
+    if (p_more) producer_setup();
+    // requests the next slab of the stream into ring stage `st`; past the end of
+    // the stream it requests out-of-range loads (zeros) so that every slab counts
+    // the same number of loads in vmcnt
+    auto produce = [&](int st) {
+        while (p_more && p_kt >= p_nk) {
+            p_more = pw.next(p);
+            if (p_more) producer_setup();
+        }
+        const int k0 = p_more ? p_kt * BK : 0;
+        const int kl = p_more ? pw.k_lim : 0;     // k_lim 0: every guard fails, nothing is read
+        if (!p_more) { dsA[2] = 0; dsB[2] = 0; }  // empty range: every load returns zeros
+        // the descriptors are wave-uniform by construction; say so to the compiler
+        // (they must sit in scalar registers for the load instruction)
+        u32x4_t ua, ub;
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) {
-        TA::issue(planA, dsA, p.lda, s * BK, k_lim, lds0 + s * SM::STAGE);
-        TB::issue(planB, dsB, p.ldb, s * BK, k_lim, lds0 + s * SM::STAGE + TA::BYTES);
-    }
-    // slab 0 has landed once at most the NS-2 younger slabs are outstanding
+        for (int i = 0; i < 4; ++i) {
+            ua[i] = __builtin_amdgcn_readfirstlane(dsA[i]);
+            ub[i] = __builtin_amdgcn_readfirstlane(dsB[i]);
+        }
+        TA::issue(planA, ua, p.lda, k0, kl, lds0 + st * SM::STAGE);
+        TB::issue(planB, ub, p.ldb, k0, kl, lds0 + st * SM::STAGE + TA::BYTES);
+        ++p_kt;
+    };
+
+    // ---- consumer ---------------------------------------------------------------
+    TileWalk<BM, BN> cw;
+    cw.start(p);
+    if (!cw.next(p)) return;       // nothing to do for this workgroup (uniform)
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) produce(s);
+    // slab 0 of the stream has landed once at most the NS-2 younger slabs are outstanding
     wait_vmcnt<(NS - 2) * SM::LOADS>();
     __syncthreads();
     typename Mma<T>::frag fa[2][TM], fb[2][TN];
@@ -387,80 +405,137 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) fb[0][j] = TB::frag(smem_raw + TA::BYTES, wn * (BN / 2) + j * 32, 0, lane);
     int stage = 0;
-    for (int kt = 0; kt < nk; ++kt) {
-        const unsigned char* a_s = smem_raw + stage * SM::STAGE;
-        const unsigned char* b_s = a_s + TA::BYTES;
-        const int next = stage == NS - 1 ? 0 : stage + 1;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const int c = ks & 1, n = c ^ 1;   // KS is even: slab kt+1 starts in buffer 0 again
-            if (ks + 1 < KS) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i) fa[n][i] = TA::frag(a_s, wm * (BM / 2) + i * 32, ks + 1, lane);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(b_s, wn * (BN / 2) + j * 32, ks + 1, lane);
-            } else {
-                // Before the last k-step of slab kt: slab kt+1 has landed once at most
-                // the NS-3 younger slabs are outstanding.  After the barrier every wave
-                // is past slab kt-1, so its stage is refilled with slab kt+NS-1, and the
-                // first fragments of slab kt+1 are fetched under this slab's last MFMAs.
-                wait_vmcnt<(NS - 3) * SM::LOADS>();
-                __syncthreads();
-#ifndef MOE_DEBUG_NOLOAD
-                const int fill = stage == 0 ? NS - 1 : stage - 1;
-                TA::issue(planA, dsA, p.lda, (kt + NS - 1) * BK, k_lim, lds0 + fill * SM::STAGE);
-                TB::issue(planB, dsB, p.ldb, (kt + NS - 1) * BK, k_lim, lds0 + fill * SM::STAGE + TA::BYTES);
-#endif
-                const unsigned char* a_n = smem_raw + next * SM::STAGE;
-#pragma unroll
-                for (int i = 0; i < TM; ++i) fa[n][i] = TA::frag(a_n, wm * (BM / 2) + i * 32, 0, lane);
-#pragma unroll
-                for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(a_n + TA::BYTES, wn * (BN / 2) + j * 32, 0, lane);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::mma(fa[c][i], fb[c][j], acc[i][j]);
-        }
-        stage = next;
-    }
-    // drain the loads still in flight (they target LDS that the epilogue reuses)
-    wait_vmcnt<0>();
-    __syncthreads();
 
-    // ---- epilogue: accumulators -> wave-private LDS strip -> row vectors -------
-    // accumulator element v of lane l in a 32x32 tile: column l%32,
-    // row 8*(v/4) + 4*(l/32) + v%4
-    float* strip = reinterpret_cast<float*>(smem_raw) + wave * 32 * ELD;
-    const int l32 = lane & 31, g = lane >> 5;
+    bool more = true;
+    while (more) {
+        const int nk = (cw.k_lim + BK - 1) / BK;
+        const size_t obase = (size_t)cw.e * p.strideO;
+        const int ncol = cw.n0 + wn * WCOLS + ec;
+        const int mrow = cw.m0 + wm * (BM / 2) + er;
+        const int m_lim = cw.m_lim;
+
+        // EPI_MUL: the saved derivative does not depend on the product.  The rows of
+        // the first two 32-row blocks are requested now and ride in registers through
+        // the main loop; the later blocks are requested while earlier ones are written.
+        constexpr int AUXB = EPI == EPI_MUL ? (TM < 2 ? TM : 2) : 1;
+        raw aux[AUXB][EPI == EPI_MUL ? 4 : 1][EPI == EPI_MUL ? NIT : 1];
+        auto fetch_aux = [&](int buf, int i) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+            for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+                for (int it = 0; it < NIT; ++it) {
+                    const int m = mrow + i * 32 + q * 8 + it * RPI;
+                    aux[buf][q][it] = (m < m_lim && ncol < p.N)
+                        ? *reinterpret_cast<const raw*>((const T*)p.aux + obase + (size_t)m * p.ldo + ncol)
+                        : Vec4io<T>::zero();
+                }
+        };
+        if constexpr (EPI == EPI_MUL) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                strip[(8 * (v >> 2) + 4 * g + (v & 3)) * ELD + j * 32 + l32] = acc[i][j][v];
-        const int mrow0 = m0 + wm * (BM / 2) + i * 32 + er;
-        if constexpr (EPI == EPI_H_DACT) {
-#pragma unroll 2
-            for (int it = 0; it < NIT; ++it) {  // (almost) rolled: few copies of the activation code
-                const float4 q = *reinterpret_cast<const float4*>(strip + (er + it * RPI) * ELD + ec);
-                float v[4] = {q.x, q.y, q.z, q.w};
-                const int m = mrow0 + it * RPI;
-                if (m < m_lim && ncol < p.N)
-                    epilogue4<T, EPI, ACT>(p, obase + (size_t)m * p.ldo + ncol, v, Vec4io<T>::zero());
+            for (int i = 0; i < AUXB; ++i) fetch_aux(i, i);
+        }
+
+        f32x16_t acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+        for (int kt = 0; kt < nk; ++kt) {
+            const unsigned char* a_s = smem_raw + stage * SM::STAGE;
+            const unsigned char* b_s = a_s + TA::BYTES;
+            const int next = stage == NS - 1 ? 0 : stage + 1;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int c = ks & 1, n = c ^ 1;   // KS is even: every slab starts in buffer 0
+                if (ks + 1 < KS) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) fa[n][i] = TA::frag(a_s, wm * (BM / 2) + i * 32, ks + 1, lane);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(b_s, wn * (BN / 2) + j * 32, ks + 1, lane);
+                } else {
+                    // Before the last k-step of a slab: the next slab of the stream (this
+                    // tile's or the next tile's first) has landed once at most the NS-3
+                    // younger slabs -- and whatever was issued after them -- are
+                    // outstanding.  After the barrier every wave is past the previous
+                    // slab, so its stage is refilled, and the next slab's first fragments
+                    // are fetched under this slab's last MFMAs.
+                    wait_vmcnt<(NS - 3) * SM::LOADS>();
+                    __syncthreads();
+                    produce(stage == 0 ? NS - 1 : stage - 1);
+                    const unsigned char* a_n = smem_raw + next * SM::STAGE;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) fa[n][i] = TA::frag(a_n, wm * (BM / 2) + i * 32, 0, lane);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(a_n + TA::BYTES, wn * (BN / 2) + j * 32, 0, lane);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::mma(fa[c][i], fb[c][j], acc[i][j]);
             }
-        } else {
+            stage = next;
+        }
+
+        // ---- epilogue: accumulators -> wave-private LDS strip -> row vectors --------
+        // accumulator element v of lane l in a 32x32 tile: column l%32,
+        // row 8*(v/4) + 4*(l/32) + v%4; strip s = (i, q) holds rows i*32 + 8q .. +7
 #pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                const float4 q = *reinterpret_cast<const float4*>(strip + (er + it * RPI) * ELD + ec);
-                float v[4] = {q.x, q.y, q.z, q.w};
-                const int m = mrow0 + it * RPI;
-                if (m < m_lim && ncol < p.N)
-                    epilogue4<T, EPI, ACT>(p, obase + (size_t)m * p.ldo + ncol, v, aux[EPI == EPI_MUL ? i : 0][EPI == EPI_MUL ? it : 0]);
+        for (int i = 0; i < TM; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        strip[(4 * g + r) * ELD + j * 32 + l32] = acc[i][j][4 * q + r];
+                const int m_strip = mrow + i * 32 + q * 8;
+                if constexpr (EPI == EPI_H_DACT) {
+#pragma unroll 1
+                    for (int it = 0; it < NIT; ++it) {  // rolled: one copy of the activation code per strip
+                        const float4 w = *reinterpret_cast<const float4*>(strip + (er + it * RPI) * ELD + ec);
+                        float v[4] = {w.x, w.y, w.z, w.w};
+                        const int m = m_strip + it * RPI;
+                        if (m < m_lim && ncol < p.N)
+                            epilogue4<T, EPI, ACT>(p, obase + (size_t)m * p.ldo + ncol, v, Vec4io<T>::zero());
+                    }
+                } else {
+#pragma unroll
+                    for (int it = 0; it < NIT; ++it) {
+                        const float4 w = *reinterpret_cast<const float4*>(strip + (er + it * RPI) * ELD + ec);
+                        float v[4] = {w.x, w.y, w.z, w.w};
+                        const int m = m_strip + it * RPI;
+                        if (m < m_lim && ncol < p.N)
+                            epilogue4<T, EPI, ACT>(p, obase + (size_t)m * p.ldo + ncol, v,
+                                                   aux[EPI == EPI_MUL ? i % AUXB : 0][EPI == EPI_MUL ? q : 0][EPI == EPI_MUL ? it : 0]);
+                    }
+                }
+            }
+            if constexpr (EPI == EPI_MUL) {
+                if (i + AUXB < TM) fetch_aux(i % AUXB, i + AUXB);   // the buffer just used is free again
             }
         }
+        more = cw.next(p);
     }
+    // the zero-fill loads requested past the end of the stream target this
+    // workgroup's LDS: wait for them before the workgroup retires
+    wait_vmcnt<0>();
+}
+
+// Number of compute units (cached; the library keeps no other state).
+static int num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
 }
 
 template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT = 0>
@@ -470,6 +545,11 @@ static void launch_gemm(GemmArgs p, int E, hipStream_t st) {
     p.tiles_n = ceil_div(p.N, BN);
     p.total_tiles = E * p.tiles_m * p.tiles_n;
     p.tiles_per_xcd = ceil_div(p.total_tiles, 8);
+    // one persistent workgroup per CU (its LDS footprint allows no second one),
+    // in groups of 8 so that every XCD gets the same number
+    int per_xcd = num_cus() / 8;
+    if (per_xcd < 1) per_xcd = 1;
+    if (per_xcd > p.tiles_per_xcd) per_xcd = p.tiles_per_xcd;
     const size_t smem = SM::BYTES;
     auto kern = grouped_gemm_kernel<T, BM, BN, BK, A_KC, B_KC, EPI, ACT>;
     if (smem > 64 * 1024) {
@@ -478,7 +558,7 @@ static void launch_gemm(GemmArgs p, int E, hipStream_t st) {
             (const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         (void)attr;
     }
-    kern<<<p.tiles_per_xcd * 8, 256, smem, st>>>(p);
+    kern<<<per_xcd * 8, 256, smem, st>>>(p);
 }
 
 size_t ffn_bwd_ws_bytes(const moe_shape* s) {
