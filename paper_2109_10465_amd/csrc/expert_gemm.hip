@@ -14,7 +14,9 @@
 // either k-contiguous in memory (KC) or r-contiguous (!KC); no transposed copy
 // of any tensor is ever materialised.
 //
-// Structure of a workgroup (4 waves, 2 x 2; one persistent workgroup per CU):
+// Structure of a workgroup (bf16: 8 waves, 2 x 4, two per SIMD so that one wave's
+// LDS waits and epilogue math hide behind the other's MFMAs; fp32: 4 waves, 2 x 2;
+// one persistent workgroup per CU):
 //   * walks BM x BN output tiles; workgroup w serves XCD w % 8 and that XCD's
 //     contiguous run of tiles (= whole experts), so co-resident tiles share
 //     operand panels in the XCD's L2; the slabs of all its tiles form one stream
@@ -26,7 +28,7 @@
 //     of MFMA work; the buffer range check supplies the zero fill for rows
 //     >= n_e (no branches in the loop); LDS tiles are unpadded and XOR-swizzled
 //     in 16-byte units so that fragment reads are bank-conflict free;
-//   * each wave accumulates (BM/2) x (BN/2) in 32x32 MFMA tiles
+//   * each wave accumulates (BM/2) x (BN/NWN) in 32x32 MFMA tiles
 //     (bf16: v_mfma_f32_32x32x16_bf16, fp32: v_mfma_f32_32x32x2_f32); !KC bf16
 //     operands are read from LDS with the transposing ds_read_b64_tr_b16;
 //   * the epilogue passes the accumulators through LDS so that every global
@@ -113,22 +115,22 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // LDS tile of one operand: BR rows (r) x BK reduction entries, unpadded, as
-// 16-byte slots; slot p is filled by thread p % 256 in its (p / 256)-th load.
+// 16-byte slots; slot p is filled by thread p % NT in its (p / NT)-th load.
 //   KC : LDS row = r (BK entries),  slot = r*CPR + (chunk ^ swz(r))
 //   !KC: LDS row = k (BR entries),  slot = k*CPR + (chunk ^ swz(k))
 // swz: KC  -> consecutive rows that share a 256-byte bank window get distinct
 //             chunk positions (16-byte fragment reads of 16 rows hit 64 banks);
 //      !KC -> rows k, k+1, k+2, k+3 are shifted by 64 bytes each (the
 //             transposing 8-byte reads of 4 rows x 64 bytes hit 64 banks).
-template <typename T, int BR, int BK, bool KC> struct Tile {
+template <typename T, int BR, int BK, bool KC, int NT> struct Tile {
     static constexpr int CN = 16 / (int)sizeof(T);           // elements per slot
     static constexpr int CPR = (KC ? BK : BR) / CN;          // slots per LDS row
     static constexpr int ROWS = KC ? BR : BK;
     static constexpr int SLOTS = ROWS * CPR;
-    static constexpr int PER_THREAD = SLOTS / 256;
+    static constexpr int PER_THREAD = SLOTS / NT;
     static constexpr int BYTES = SLOTS * 16;
     static constexpr int WIN = CPR >= 16 ? 1 : 16 / CPR;     // rows per 256-byte window
-    static_assert(SLOTS % 256 == 0, "tile must be a multiple of 256 slots");
+    static_assert(SLOTS % NT == 0, "tile must be a multiple of the workgroup size in slots");
     static_assert((CPR & (CPR - 1)) == 0, "slots per row must be a power of two");
 
     __device__ static __forceinline__ int swz(int row) {
@@ -142,7 +144,7 @@ template <typename T, int BR, int BK, bool KC> struct Tile {
     __device__ static __forceinline__ void plan(Plan& pl, int ld, int r0, int r_lim) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
-            const int p = threadIdx.x + i * 256;
+            const int p = threadIdx.x + i * NT;
             const int row = p / CPR, c = (p % CPR) ^ swz(row);
             if (KC) {
                 pl.voff[i] = (uint32_t)((r0 + row) * ld + c * CN) * (uint32_t)sizeof(T);
@@ -167,7 +169,7 @@ template <typename T, int BR, int BK, bool KC> struct Tile {
         for (int i = 0; i < PER_THREAD; ++i) {
             uint32_t off = pl.voff[i] + kstep;
             if (KC) off = pl.kcol[i] + k0 < k_lim ? off : OOB_OFFSET;
-            load_to_lds(ds, off, __builtin_amdgcn_readfirstlane(wave_base + i * 4096));
+            load_to_lds(ds, off, __builtin_amdgcn_readfirstlane(wave_base + i * NT * 16));
         }
     }
     // LDS -> MFMA operand for the 32 tile rows rbase..rbase+31 (this lane: row
@@ -265,16 +267,18 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& p, size_t o, float (&v
     }
 }
 
-template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC>
+// NWN = wavefronts along N (2 or 4); always 2 along M.
+template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int NWN>
 struct GemmSmem {
-    typedef Tile<T, BM, BK, A_KC> TA;
-    typedef Tile<T, BN, BK, B_KC> TB;
+    static constexpr int NT = 128 * NWN;        // threads per workgroup
+    typedef Tile<T, BM, BK, A_KC, NT> TA;
+    typedef Tile<T, BN, BK, B_KC, NT> TB;
     static constexpr int STAGE = TA::BYTES + TB::BYTES;
     static constexpr int NSTAGE = 4;            // LDS ring: 1 slab being multiplied + 3 in flight
-    static constexpr int EPI_LD = BN / 2 + 8;   // floats per staged epilogue row (4 rows apart -> other bank half)
+    static constexpr int EPI_LD = BN / NWN + 8; // floats per staged epilogue row (4 rows apart -> other bank half)
     static constexpr int EPI_ROWS = 8;          // one accumulator register quad of both lane halves
     static constexpr size_t RING = (size_t)NSTAGE * STAGE;
-    static constexpr size_t EPILOGUE = 4 * EPI_ROWS * (size_t)EPI_LD * sizeof(float);  // wave-private strips
+    static constexpr size_t EPILOGUE = 2 * NWN * EPI_ROWS * (size_t)EPI_LD * sizeof(float);  // wave-private strips
     static constexpr size_t BYTES = RING + EPILOGUE;   // the epilogue never touches the ring
     static constexpr int LOADS = TA::PER_THREAD + TB::PER_THREAD;  // per thread per slab
     static_assert((NSTAGE - 1) * LOADS < 64, "vmcnt is a 6-bit counter");
@@ -322,26 +326,26 @@ struct TileWalk {
 // them as one stream through the LDS ring, so the first slabs of the next tile
 // are already resident when the epilogue of the current one ends, and no
 // workgroup launch or cold first load sits between two tiles.
-template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT>
-__global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
-    typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC> SM;
+template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT, int NWN>
+__global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs p) {
+    typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC, NWN> SM;
     typedef typename SM::TA TA;
     typedef typename SM::TB TB;
     typedef typename Vec4io<T>::raw raw;
-    constexpr int TM = BM / 64, TN = BN / 64;  // 32x32 MFMA tiles per wave (2x2 waves)
+    constexpr int TM = BM / 64, TN = BN / (32 * NWN);  // 32x32 MFMA tiles per wave (2 x NWN waves)
     constexpr int KS = BK / Mma<T>::KSTEP;
     constexpr int NS = SM::NSTAGE;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / NWN, wn = wave % NWN;
     const int l32 = lane & 31, g = lane >> 5;
 
     // epilogue geometry: the wave's (BM/2) x (BN/2) sub-tile leaves in strips of 8
     // rows; a lane owns 4 consecutive columns of RPI-strided rows
     constexpr int ELD = SM::EPI_LD;
-    constexpr int WCOLS = BN / 2;
+    constexpr int WCOLS = BN / NWN;
     constexpr int LPR = WCOLS / 4;                // lanes per staged row
     constexpr int RPI = 64 / LPR;                 // rows per wave instruction
     constexpr int NIT = SM::EPI_ROWS / RPI;       // row vectors per lane per strip
@@ -403,7 +407,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) fa[0][i] = TA::frag(smem_raw, wm * (BM / 2) + i * 32, 0, lane);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = TB::frag(smem_raw + TA::BYTES, wn * (BN / 2) + j * 32, 0, lane);
+    for (int j = 0; j < TN; ++j) fb[0][j] = TB::frag(smem_raw + TA::BYTES, wn * WCOLS + j * 32, 0, lane);
     int stage = 0;
 
     bool more = true;
@@ -454,7 +458,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
 #pragma unroll
                     for (int i = 0; i < TM; ++i) fa[n][i] = TA::frag(a_s, wm * (BM / 2) + i * 32, ks + 1, lane);
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(b_s, wn * (BN / 2) + j * 32, ks + 1, lane);
+                    for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(b_s, wn * WCOLS + j * 32, ks + 1, lane);
                 } else {
                     // Before the last k-step of a slab: the next slab of the stream (this
                     // tile's or the next tile's first) has landed once at most the NS-3
@@ -469,7 +473,7 @@ __global__ __launch_bounds__(256) void grouped_gemm_kernel(const GemmArgs p) {
 #pragma unroll
                     for (int i = 0; i < TM; ++i) fa[n][i] = TA::frag(a_n, wm * (BM / 2) + i * 32, 0, lane);
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(a_n + TA::BYTES, wn * (BN / 2) + j * 32, 0, lane);
+                    for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(a_n + TA::BYTES, wn * WCOLS + j * 32, 0, lane);
                 }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -538,9 +542,13 @@ static int num_cus() {
     return n;
 }
 
+#ifndef MOE_GEMM_NWN
+#define MOE_GEMM_NWN 4
+#endif
 template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT = 0>
 static void launch_gemm(GemmArgs p, int E, hipStream_t st) {
-    typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC> SM;
+    constexpr int NWN = sizeof(T) == 2 ? MOE_GEMM_NWN : 2;
+    typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC, NWN> SM;
     p.tiles_m = ceil_div(p.M, BM);
     p.tiles_n = ceil_div(p.N, BN);
     p.total_tiles = E * p.tiles_m * p.tiles_n;
@@ -551,14 +559,14 @@ static void launch_gemm(GemmArgs p, int E, hipStream_t st) {
     if (per_xcd < 1) per_xcd = 1;
     if (per_xcd > p.tiles_per_xcd) per_xcd = p.tiles_per_xcd;
     const size_t smem = SM::BYTES;
-    auto kern = grouped_gemm_kernel<T, BM, BN, BK, A_KC, B_KC, EPI, ACT>;
+    auto kern = grouped_gemm_kernel<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN>;
     if (smem > 64 * 1024) {
         // opt in (once per kernel instance) to more than 64 KB of the CU's 160 KB LDS
         static const hipError_t attr = hipFuncSetAttribute(
             (const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         (void)attr;
     }
-    kern<<<per_xcd * 8, 256, smem, st>>>(p);
+    kern<<<per_xcd * 8, SM::NT, smem, st>>>(p);
 }
 
 size_t ffn_bwd_ws_bytes(const moe_shape* s) {
