@@ -23,6 +23,9 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(
     const int t0 = blockIdx.x * GL_TB;
     constexpr int CN = Chunk<T>::N;
     constexpr int CPR = GL_DK / CN;  // 16-byte chunks per token row of the slab
+    const int rows_here = min(GL_TB, Tn - t0);
+    const __amdgpu_buffer_rsrc_t rs_x = buf_rsrc(x + (size_t)t0 * d, (size_t)rows_here * d * sizeof(T));
+    const __amdgpu_buffer_rsrc_t rs_w = buf_rsrc(Wg, (size_t)d * E * 4);
     constexpr int XPT = GL_TB * CPR / 256;   // x chunks per thread per slab
     constexpr int WPT = GL_DK * 32 / 256;    // Wg entries per thread per slab
     static_assert(GL_TB * CPR % 256 == 0, "slab must divide over the workgroup");
@@ -30,18 +33,18 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(
         float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
         float xr[XPT][CN], wr[WPT];
         // slab k0 -> registers (zero outside the tensors)
-        auto fetch = [&](int k0) {
+        auto fetch = [&](int k0) {   // branch free: out-of-range lanes read zeros
 #pragma unroll
             for (int j = 0; j < XPT; ++j) {
                 const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
-#pragma unroll
-                for (int i = 0; i < CN; ++i) xr[j][i] = 0.0f;
-                if (t0 + r < Tn && k0 + cc * CN < d) Chunk<T>::load(x + (size_t)(t0 + r) * d + k0 + cc * CN, xr[j]);
+                const bool ok = k0 + cc * CN < d;    // rows beyond T fall outside rs_x
+                BufChunk<T>::load(rs_x, ok ? (uint32_t)((r * d + k0 + cc * CN) * sizeof(T)) : BUF_OOB, xr[j]);
             }
 #pragma unroll
             for (int j = 0; j < WPT; ++j) {
                 const int c = tid + j * 256, r = c >> 5, e = c & 31;
-                wr[j] = (k0 + r < d && e0 + e < E) ? Wg[(size_t)(k0 + r) * E + e0 + e] : 0.0f;
+                const bool ok = e0 + e < E;          // rows beyond d fall outside rs_w
+                wr[j] = buf_load_f32(rs_w, ok ? (uint32_t)(((k0 + r) * E + e0 + e) * 4) : BUF_OOB);
             }
         };
         fetch(0);
@@ -162,6 +165,9 @@ static inline int gw_chunks(const moe_shape* s) {
     int want = ceil_div(1024, ceil_div(s->d_model, GW_DT));
     int maxc = ceil_div(s->T, 256);
     int n = want < maxc ? want : maxc;
+    // one chunk's rows of x are addressed with 32-bit byte offsets: keep it below 1 GiB
+    const int minc = (int)(((size_t)s->T * s->d_model * 4 + ((size_t)1 << 30) - 1) >> 30);
+    if (n < minc) n = minc;
     return n < 1 ? 1 : n;
 }
 size_t gate_logits_bwd_ws_bytes(const moe_shape* s) {
@@ -181,24 +187,26 @@ __global__ __launch_bounds__(256) void gate_dwg_partial_kernel(
     const int tbeg = blockIdx.y * tok_per_chunk;
     const int tend = min(Tn, tbeg + tok_per_chunk);
     constexpr int CN = Chunk<T>::N, CPR = GW_DT / CN;
+    const int nrows = max(tend - tbeg, 0);
+    const __amdgpu_buffer_rsrc_t rs_x = buf_rsrc(x + (size_t)tbeg * d, (size_t)nrows * d * sizeof(T));
+    const __amdgpu_buffer_rsrc_t rs_d = buf_rsrc(dlogits + (size_t)tbeg * E, (size_t)nrows * E * 4);
     constexpr int XPT = GW_TT * CPR / 256 > 0 ? GW_TT * CPR / 256 : 1;
     constexpr int DPT = GW_TT * 32 / 256;
     for (int e0 = 0; e0 < E; e0 += 32) {
         float acc[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
         float xr[XPT][CN], dr[DPT];
-        auto fetch = [&](int ts) {
+        auto fetch = [&](int ts) {   // branch free: out-of-range lanes read zeros
 #pragma unroll
             for (int j = 0; j < XPT; ++j) {
                 const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
-#pragma unroll
-                for (int q = 0; q < CN; ++q) xr[j][q] = 0.0f;
-                if (c < GW_TT * CPR && ts + r < tend && i0 + cc * CN < d)
-                    Chunk<T>::load(x + (size_t)(ts + r) * d + i0 + cc * CN, xr[j]);
+                const bool ok = c < GW_TT * CPR && i0 + cc * CN < d;   // rows beyond tend fall outside rs_x
+                BufChunk<T>::load(rs_x, ok ? (uint32_t)(((ts - tbeg + r) * d + i0 + cc * CN) * sizeof(T)) : BUF_OOB, xr[j]);
             }
 #pragma unroll
             for (int j = 0; j < DPT; ++j) {
                 const int c = tid + j * 256, r = c >> 5, e = c & 31;
-                dr[j] = (ts + r < tend && e0 + e < E) ? dlogits[(size_t)(ts + r) * E + e0 + e] : 0.0f;
+                const bool ok = e0 + e < E;
+                dr[j] = buf_load_f32(rs_d, ok ? (uint32_t)(((ts - tbeg + r) * E + e0 + e) * 4) : BUF_OOB);
             }
         };
         fetch(tbeg);
@@ -277,9 +285,19 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(int Tn, int d, int E,
     constexpr int LD = GX_TB + 4;
     const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
     const int t0 = blockIdx.x * GX_TB;
-    for (int c = tid; c < GX_TB * E; c += 256) {
-        const int r = c / E, e = c - r * E;
-        dls[e * LD + r] = t0 + r < Tn ? dlogits[(size_t)t0 * E + c] : 0.0f;
+    const int rows_here = min(GX_TB, Tn - t0);
+    const __amdgpu_buffer_rsrc_t rs_dl = buf_rsrc(dlogits + (size_t)t0 * E, (size_t)rows_here * E * 4);
+    const __amdgpu_buffer_rsrc_t rs_w = buf_rsrc(Wg, (size_t)d * E * 4);
+    const __amdgpu_buffer_rsrc_t rs_dx = buf_rsrc(dx + (size_t)t0 * d, (size_t)rows_here * d * sizeof(T));
+    for (int c0 = 0; c0 < GX_TB * E; c0 += 1024) {   // 4 loads in flight; rows beyond T read zeros
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = buf_load_f32(rs_dl, (uint32_t)(c0 + u * 256 + tid) * 4);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * 256 + tid, r = c / E, e = c - r * E;
+            if (c < GX_TB * E) dls[e * LD + r] = v[u];
+        }
     }
     // E <= 64: the Wg slab of the next 64 columns is prefetched into registers and
     // the dx values to be updated are requested before the FMA loop, so neither
@@ -287,21 +305,27 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(int Tn, int d, int E,
     typedef typename Vec4io<T>::raw raw;
     constexpr int WPT = 64 * 64 / 256;
     float wr[WPT];
+    // thread -> column rows r = tid/16 + 16*jr, experts e = tid%16 + 16*je of the 64 x 64 slab:
+    // 64 contiguous bytes per row and load, no divisions
+    const int wr_r = tid >> 4, wr_e = tid & 15;
     auto fetch_w = [&](int i0, int e0, int ne) {
 #pragma unroll
-        for (int j = 0; j < WPT; ++j) {
-            const int c = tid + j * 256;
-            const int r = c / ne, e = c - r * ne;
-            wr[j] = (c < 64 * ne && i0 + r < d) ? Wg[(size_t)(i0 + r) * E + e0 + e] : 0.0f;
-        }
-    };
-    auto commit_w = [&](int ne) {
+        for (int jr = 0; jr < 4; ++jr)
 #pragma unroll
-        for (int j = 0; j < WPT; ++j) {
-            const int c = tid + j * 256;
-            const int r = c / ne, e = c - r * ne;
-            if (c < 64 * ne) wgs[e * LD + r] = wr[j];
-        }
+            for (int je = 0; je < 4; ++je) {
+                const int r = wr_r + 16 * jr, e = wr_e + 16 * je;
+                // rows beyond d fall outside rs_w
+                wr[jr * 4 + je] = buf_load_f32(rs_w, e < ne ? (uint32_t)(((i0 + r) * E + e0 + e) * 4) : BUF_OOB);
+            }
+    };
+    auto commit_w = [&](int ne) {   // experts >= ne are stored as zeros and never read
+#pragma unroll
+        for (int jr = 0; jr < 4; ++jr)
+#pragma unroll
+            for (int je = 0; je < 4; ++je) {
+                const int r = wr_r + 16 * jr, e = wr_e + 16 * je;
+                if (e < min(E, 64)) wgs[e * LD + r] = wr[jr * 4 + je];
+            }
     };
     const bool single = E <= 64;
     if (single) fetch_w(0, 0, E);
@@ -315,8 +339,8 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(int Tn, int d, int E,
         raw cur_raw[4];
 #pragma unroll
         for (int a = 0; a < 4; ++a) {
-            const int t = t0 + ty * 4 + a;
-            cur_raw[a] = (i < d && t < Tn) ? *reinterpret_cast<const raw*>(dx + (size_t)t * d + i) : Vec4io<T>::zero();
+            // rows beyond T fall outside rs_dx
+            cur_raw[a] = Vec4buf<T>::load(rs_dx, i < d ? (uint32_t)(((ty * 4 + a) * d + i) * sizeof(T)) : BUF_OOB);
         }
         for (int e0 = 0; e0 < E; e0 += 64) {
             const int ne = min(64, E - e0);
@@ -345,18 +369,14 @@ __global__ __launch_bounds__(256) void gate_dx_kernel(int Tn, int d, int E,
                 }
             }
         }
-        if (i < d) {
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int t = t0 + ty * 4 + a;
-                if (t < Tn) {
-                    float cur[4];
-                    Vec4io<T>::unpack(cur_raw[a], cur);
+        for (int a = 0; a < 4; ++a) {   // stores beyond T or d are dropped by the range check
+            float cur[4];
+            Vec4io<T>::unpack(cur_raw[a], cur);
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) cur[b] += acc[a][b];
-                    *reinterpret_cast<raw*>(dx + (size_t)t * d + i) = Vec4io<T>::pack(cur);
-                }
-            }
+            for (int b = 0; b < 4; ++b) cur[b] += acc[a][b];
+            Vec4buf<T>::store(rs_dx, i < d ? (uint32_t)(((ty * 4 + a) * d + i) * sizeof(T)) : BUF_OOB,
+                                 Vec4io<T>::pack(cur));
         }
     }
 }

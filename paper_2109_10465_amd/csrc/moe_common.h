@@ -86,6 +86,61 @@ template <> struct Vec4io<bf16_t> {
     }
 };
 
+// ---- raw buffer access: the descriptor's range check replaces per-lane branches ----
+// Loads beyond `bytes` return 0 and stores beyond it are dropped, so a guard is
+// folded into the offset (BUF_OOB for "not this lane") and the code stays branch free.
+typedef unsigned int u32x2_buf_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4_buf_t __attribute__((ext_vector_type(4)));
+#define BUF_OOB 0x80000000u   // beyond every descriptor built here (ranges stay below 2 GiB)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buf_rsrc(const void* p, size_t bytes) {
+    const uint32_t n = bytes < 0x7fffffffull ? (uint32_t)bytes : 0x7fffffffu;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)n, 0x00020000);
+}
+__device__ __forceinline__ float buf_load_f32(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0));
+}
+// 16 bytes of activations at byte offset off, widened to fp32
+template <typename T> struct BufChunk;
+template <> struct BufChunk<float> {
+    __device__ static __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t off, float (&v)[4]) {
+        const u32x4_buf_t q = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(q[i]);
+    }
+};
+template <> struct BufChunk<bf16_t> {
+    __device__ static __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t off, float (&v)[8]) {
+        const u32x4_buf_t q = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(q[i] << 16);
+            v[2 * i + 1] = __uint_as_float(q[i] & 0xffff0000u);
+        }
+    }
+};
+
+template <typename T> struct Vec4buf;
+template <> struct Vec4buf<float> {
+    __device__ static __forceinline__ float4 load(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        const u32x4_buf_t q = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+        return make_float4(__uint_as_float(q[0]), __uint_as_float(q[1]), __uint_as_float(q[2]), __uint_as_float(q[3]));
+    }
+    __device__ static __forceinline__ void store(__amdgpu_buffer_rsrc_t r, uint32_t off, float4 v) {
+        u32x4_buf_t q = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+        __builtin_amdgcn_raw_buffer_store_b128(q, r, off, 0, 0);
+    }
+};
+template <> struct Vec4buf<bf16_t> {
+    __device__ static __forceinline__ uint2 load(__amdgpu_buffer_rsrc_t r, uint32_t off) {
+        const u32x2_buf_t q = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+        return make_uint2(q[0], q[1]);
+    }
+    __device__ static __forceinline__ void store(__amdgpu_buffer_rsrc_t r, uint32_t off, uint2 v) {
+        u32x2_buf_t q = {v.x, v.y};
+        __builtin_amdgcn_raw_buffer_store_b64(q, r, off, 0, 0);
+    }
+};
+
 // ---- wave64 reductions (butterfly: every lane ends with the same bits) ------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
