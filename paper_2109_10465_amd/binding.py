@@ -39,6 +39,9 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise MoeError(f"{LIB_PATH} is missing: build it with `python -m paper_2109_10465_amd.build`")
+        # torch first: the process must hold ONE HIP runtime, the one torch's streams
+        # and allocations belong to; the library then binds to that same runtime
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32
         shp = ctypes.POINTER(MoeShape)

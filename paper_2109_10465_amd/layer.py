@@ -53,10 +53,15 @@ class MoELayer:
             raise B.MoeError("unsupported shape")
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
-    def forward(self, x, Wg, bias, W1, W2, rts_keys):
+    def forward(self, x, Wg, bias, W1, W2, rts_keys, logits=None):
+        """logits: optional precomputed [T,E] fp32 gate logits; the projection call is
+        then skipped and routing runs on exactly these values."""
         s = self.shape
         self._saved = (x, Wg, W1, W2)
-        B.moe_gate_logits(s, x, Wg, bias, self.logits)
+        if logits is None:
+            B.moe_gate_logits(s, x, Wg, bias, self.logits)
+        else:
+            self.logits.copy_(logits)
         B.moe_gate_route(s, self.logits, rts_keys, self.probs, self.expert_idx, self.gate_w,
                          self.slot, self.expert_count, self.expert_demand, self.slot_src, self.ws)
         B.moe_dispatch(s, x, self.slot_src, self.expert_count, self.xd)
@@ -77,6 +82,6 @@ class MoELayer:
         B.moe_gate_logits_bwd(s, x, Wg, self.dlogits, self.dWg, self.dx, self.ws)
         return self.dx, self.dWg, self.dW1, self.dW2
 
-    def step(self, x, Wg, bias, W1, W2, rts_keys, dy):
-        self.forward(x, Wg, bias, W1, W2, rts_keys)
+    def step(self, x, Wg, bias, W1, W2, rts_keys, dy, logits=None):
+        self.forward(x, Wg, bias, W1, W2, rts_keys, logits)
         return self.backward(dy)

@@ -19,34 +19,73 @@ SMALL = ["logits", "probs", "expert_idx", "gate_w", "slot", "expert_count", "exp
 
 
 def run_big(w):
+    """Two runs on one layer object: the chained path (GPU projection feeding the
+    router), of which the logits and the routing are kept, then the same layer
+    routed on the oracle's fp32 logits, whose outputs are the ones sampled."""
     t = time.time()
     d = I.make_inputs(w, seed=0)
+    _, lg32 = G.oracle_logits(d)
     print(f"[gen] {w.name} {time.time() - t:.1f}s", flush=True)
-    layer, _ = None, None
     from paper_2109_10465_amd.layer import MoELayer
     layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act)
     dev = {n: G.to_dev(d[n], w.dtype) for n in ["x", "dy", "W1", "W2"]}
     Wg, bias, keys = G.to_dev(d["Wg"], I.F32), G.to_dev(d["bias"], I.F32), G.to_dev(d["rts_keys"], I.F32)
-    print(f"[gpu] {w.name} fwd+bwd", flush=True)
+    print(f"[gpu] {w.name} fwd+bwd, chained", flush=True)
     layer.step(dev["x"], Wg, bias, dev["W1"], dev["W2"], keys, dev["dy"])
+    torch.cuda.synchronize()
+    chained = {n: G.host(getattr(layer, n)) for n in ["logits"] + G.INT_NAMES}
+    print(f"[gpu] {w.name} fwd+bwd, routed on the oracle's logits", flush=True)
+    layer.step(dev["x"], Wg, bias, dev["W1"], dev["W2"], keys, dev["dy"], G.to_dev(lg32, I.F32))
     torch.cuda.synchronize()
     got = {n: G.host(getattr(layer, n)) for n in SMALL}
     fetch = lambda name, e: G.host(getattr(layer, name)[e])
-    return d, got, fetch
+    return d, got, fetch, chained, lg32
 
 
 @pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
 def test_full_size_sampled(name):
     w = I.WORKLOADS[name]
-    d, got, fetch = run_big(w)
+    d, got, fetch, chained, lg32 = run_big(w)
     t = time.time()
-    errs = G.check_sampled(w, d, got, n_tokens=96 if name == "cfg5" else 192,
-                           n_rows=24 if name == "cfg5" else 48, fetch_expert=fetch)
-    print(f"[oracle] {name} sampled check {time.time() - t:.1f}s", {k: f"{v:.2e}" for k, v in errs.items()},
-          flush=True)
+    errs, route = G.check_sampled(w, d, got, n_tokens=96 if name == "cfg5" else 192,
+                                  n_rows=24 if name == "cfg5" else 48, fetch_expert=fetch)
+    near = G.check_chained_routing(w, d, chained, lg32, route)
+    print(f"[oracle] {name} sampled check {time.time() - t:.1f}s, near-tied tokens {near}",
+          {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
     if name == "cfg4":      # Zipf skew: many experts overflow, many tokens are dropped
         assert (got["expert_demand"] > w.capacity).sum() >= 5
         assert (got["slot"] < 0).mean() > 0.3
+
+
+@pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
+def test_gate_projection_backward_full_size(name):
+    """dWg = x^T dlogits and dx += dlogits Wg^T at full size on generator-made
+    dlogits (a third of the rows zero, like dropped tokens) and a preset dx."""
+    from oracle import moe_oracle as O
+    from paper_2109_10465_amd import binding as B
+    w = I.WORKLOADS[name]
+    d = I.make_inputs(w, seed=0, with_weights=False)
+    rng = np.random.default_rng(5)
+    dl = (rng.standard_normal((w.T, w.E)) * 0.05).astype(np.float32)
+    dl[rng.random(w.T) < 1.0 / 3.0] = 0.0
+    dx0 = d["dy"]                                   # any seeded tensor of the activation type
+    shape = B.make_shape(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act)
+    x, dx = G.to_dev(d["x"], w.dtype), G.to_dev(dx0, w.dtype).clone()
+    Wg, dld = G.to_dev(d["Wg"], I.F32), G.to_dev(dl, I.F32)
+    dWg = torch.empty((w.d_model, w.E), dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.moe_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    print(f"[gpu] {name} gate projection backward", flush=True)
+    B.moe_gate_logits_bwd(shape, x, Wg, dld, dWg, dx, ws)
+    torch.cuda.synchronize()
+    dWg_ref, dx_ref = O.gate_logits_bwd(d["x"], d["Wg"], dl)
+    assert G.rel_l2(G.host(dWg), dWg_ref) <= 1e-5
+    assert G.rel_l2(G.host(dx), dx0 + dx_ref) <= G.TOL[w.dtype]
+    # the increment itself, not hidden by the preset: a second call on a zeroed dx
+    dz = torch.zeros_like(dx)
+    B.moe_gate_logits_bwd(shape, x, Wg, dld, dWg, dz, ws)
+    torch.cuda.synchronize()
+    assert G.rel_l2(G.host(dz), dx_ref) <= G.TOL[w.dtype]
+    assert G.rel_l2(G.host(dWg), dWg_ref) <= 1e-5
 
 
 def test_cfg3_whole_oracle():

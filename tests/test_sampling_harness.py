@@ -40,3 +40,34 @@ def test_sampled_checker_accepts_the_oracle_and_rejects_planted_errors(k):
     bad["slot"][0, 0] ^= 1
     with pytest.raises(AssertionError):
         G.check_sampled(w, d, bad, n_tokens=60, n_cols=8, n_rows=10, fetch_expert=fetch)
+
+
+def test_chained_routing_checker_near_ties_and_planted_errors():
+    """The checker of the chained path accepts a run whose logits differ in the
+    last bits, accepts either order of a near-tied pair (with the slots that
+    follow from it), and rejects a wrong choice on a clear-cut token."""
+    w = I.small("chain", 300, 16, 24, 6, 2, 70, I.F32, I.GELU)
+    d = I.make_inputs(w, seed=4)
+    d["Wg"] = d["Wg"] * 10
+    lg = O.gate_logits(d["x"], d["Wg"], d["bias"]).astype(np.float32)
+    # plant a near tie: token 5's best two logits differ by one fp32 ulp
+    e = O.top_k(lg, 2)
+    lg[5, e[5, 1]] = np.nextafter(lg[5, e[5, 0]], np.float32(-np.inf))
+    route_of = lambda eidx: dict(zip(["slot", "expert_count", "expert_demand", "slot_src"],
+                                     O.route(eidx, d["rts_keys"], w.E, w.capacity)), expert_idx=eidx)
+    eidx = O.top_k(lg, 2)
+    ref = route_of(eidx)
+    noisy = (lg.astype(np.float64) * (1 + 2e-7 * np.sin(np.arange(lg.size)).reshape(lg.shape))).astype(np.float32)
+    got = dict(ref, logits=noisy)
+    assert G.check_chained_routing(w, d, got, lg, ref) >= 1
+    flipped = eidx.copy()
+    flipped[5] = flipped[5, ::-1]                       # the other order of the near-tied pair
+    assert G.check_chained_routing(w, d, dict(route_of(flipped), logits=noisy), lg, ref) >= 1
+    with pytest.raises(AssertionError):                  # right choice, stale slots
+        G.check_chained_routing(w, d, dict(ref, expert_idx=flipped, logits=noisy), lg, ref)
+    wrong = eidx.copy()
+    t = int(np.argmax(np.sort(lg, axis=1)[:, -1] - np.sort(lg, axis=1)[:, -2]))   # clearest winner
+    wrong[t] = wrong[t, ::-1]
+    with pytest.raises(AssertionError):
+        G.check_chained_routing(w, d, dict(route_of(wrong), logits=noisy), lg, ref)
+    assert G.check_chained_routing(w, d, dict(ref, logits=lg), lg, ref) >= 0
