@@ -24,8 +24,11 @@
 //     current tile's epilogue;
 //   * streams BK-deep slabs of both operands with 16-byte buffer loads that
 //     write straight into LDS (no register staging), NSTAGE-1 slabs ahead of
-//     the one being multiplied, so HBM/L2 latency is covered by several slabs
-//     of MFMA work; the buffer range check supplies the zero fill for rows
+//     the one being multiplied.  A stage is refilled as soon as the fragments
+//     of its last k-step sit in registers, i.e. one full slab period before
+//     the slab is needed (bf16: BK = 64, so a K-contiguous operand is fetched
+//     in 128-byte row pieces, two 64 KB stages); the buffer range check
+//     supplies the zero fill for rows
 //     >= n_e (no branches in the loop); LDS tiles are unpadded and XOR-swizzled
 //     in 16-byte units so that fragment reads are bank-conflict free;
 //   * each wave accumulates (BM/2) x (BN/NWN) in 32x32 MFMA tiles
@@ -46,7 +49,7 @@
 #define MOE_GEMM_BN 256
 #endif
 #ifndef MOE_GEMM_BK
-#define MOE_GEMM_BK 32
+#define MOE_GEMM_BK 64
 #endif
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -112,6 +115,11 @@ __device__ __forceinline__ void load_to_lds(u32x4_t desc, uint32_t voff, uint32_
 // s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in 15:14)
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
+}
+
+// the same, and every LDS operation of this wave has completed as well
+template <int N> __device__ __forceinline__ void wait_vmcnt_lgkm0() {
+    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4));
 }
 
 // LDS tile of one operand: BR rows (r) x BK reduction entries, unpadded, as
@@ -274,14 +282,18 @@ struct GemmSmem {
     typedef Tile<T, BM, BK, A_KC, NT> TA;
     typedef Tile<T, BN, BK, B_KC, NT> TB;
     static constexpr int STAGE = TA::BYTES + TB::BYTES;
-    static constexpr int NSTAGE = 4;            // LDS ring: 1 slab being multiplied + 3 in flight
+#ifndef MOE_GEMM_NS
+#define MOE_GEMM_NS 0
+#endif
+    // LDS ring: 1 slab being multiplied + NSTAGE-1 in flight (as many as fit beside the epilogue strips)
+    static constexpr int NSTAGE = MOE_GEMM_NS ? MOE_GEMM_NS : (STAGE > 48 * 1024 ? 2 : (STAGE > 32 * 1024 ? 3 : 4));
     static constexpr int EPI_LD = BN / NWN + 8; // floats per staged epilogue row (4 rows apart -> other bank half)
     static constexpr int EPI_ROWS = 8;          // one accumulator register quad of both lane halves
     static constexpr size_t RING = (size_t)NSTAGE * STAGE;
     static constexpr size_t EPILOGUE = 2 * NWN * EPI_ROWS * (size_t)EPI_LD * sizeof(float);  // wave-private strips
     static constexpr size_t BYTES = RING + EPILOGUE;   // the epilogue never touches the ring
     static constexpr int LOADS = TA::PER_THREAD + TB::PER_THREAD;  // per thread per slab
-    static_assert((NSTAGE - 1) * LOADS < 64, "vmcnt is a 6-bit counter");
+    static_assert(NSTAGE * LOADS < 64, "vmcnt is a 6-bit counter");
     static_assert((BK / Mma<T>::KSTEP) % 2 == 0, "fragment double buffering needs an even number of k-steps");
     static_assert(BYTES <= 160 * 1024, "LDS of one CU");
 };
@@ -394,14 +406,17 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
         ++p_kt;
     };
 
+#ifdef MOE_GEMM_CLOCKDBG
+    const long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
+#endif
     // ---- consumer ---------------------------------------------------------------
     TileWalk<BM, BN> cw;
     cw.start(p);
     if (!cw.next(p)) return;       // nothing to do for this workgroup (uniform)
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s) produce(s);
-    // slab 0 of the stream has landed once at most the NS-2 younger slabs are outstanding
-    wait_vmcnt<(NS - 2) * SM::LOADS>();
+    for (int s = 0; s < NS; ++s) produce(s);
+    // slab 0 of the stream has landed once at most the NS-1 younger slabs are outstanding
+    wait_vmcnt<(NS - 1) * SM::LOADS>();
     __syncthreads();
     typename Mma<T>::frag fa[2][TM], fb[2][TN];
 #pragma unroll
@@ -460,15 +475,17 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
 #pragma unroll
                     for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(b_s, wn * WCOLS + j * 32, ks + 1, lane);
                 } else {
-                    // Before the last k-step of a slab: the next slab of the stream (this
-                    // tile's or the next tile's first) has landed once at most the NS-3
-                    // younger slabs -- and whatever was issued after them -- are
-                    // outstanding.  After the barrier every wave is past the previous
-                    // slab, so its stage is refilled, and the next slab's first fragments
-                    // are fetched under this slab's last MFMAs.
-                    wait_vmcnt<(NS - 3) * SM::LOADS>();
-                    __syncthreads();
-                    produce(stage == 0 ? NS - 1 : stage - 1);
+                    // Before the last k-step of a slab: its fragments are already in
+                    // registers (requested one step ago; the wait below covers them), so once
+                    // every wave is here nobody reads this stage again and it is refilled at
+                    // once with the slab NS positions down the stream.  The next slab (this
+                    // tile's or the next tile's first) has landed once at most the NS-2
+                    // younger ones are outstanding; its first fragments are fetched under
+                    // this slab's last MFMAs.
+                    wait_vmcnt_lgkm0<(NS - 2) * SM::LOADS>();
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                    produce(stage);
                     const unsigned char* a_n = smem_raw + next * SM::STAGE;
 #pragma unroll
                     for (int i = 0; i < TM; ++i) fa[n][i] = TA::frag(a_n, wm * (BM / 2) + i * 32, 0, lane);
@@ -479,6 +496,14 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::mma(fa[c][i], fb[c][j], acc[i][j]);
+                // issue order: the fragment reads of the next k-step go out under the
+                // first MFMAs of this one, so a full step of matrix work covers their latency
+#pragma unroll
+                for (int q = 0; q < TM * TN; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // LDS reads
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                }
+                __builtin_amdgcn_sched_barrier(0);   // no MFMA drifts into the next step
             }
             stage = next;
         }
@@ -526,6 +551,12 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
     // the zero-fill loads requested past the end of the stream target this
     // workgroup's LDS: wait for them before the workgroup retires
     wait_vmcnt<0>();
+#ifdef MOE_GEMM_CLOCKDBG
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        ((long long*)p.out0)[0] = clock64() - dbg_c0;
+        ((long long*)p.out0)[1] = wall_clock64() - dbg_w0;
+    }
+#endif
 }
 
 // Number of compute units (cached; the library keeps no other state).
