@@ -295,6 +295,40 @@ def gate_bwd(dgate_w, p, expert_idx, slot):
     return p * (dp - (p * dp).sum(axis=1, keepdims=True))
 
 
+# --------------------------------------------------------------------------
+# balancing auxiliary loss                          (Sec. 5.1, "MoE setting")
+# --------------------------------------------------------------------------
+def aux_loss(p, expert_idx):
+    """Balancing loss of the gate (Sec. 5.1: an additional balancing loss, times
+    0.01, is added to the training loss; the paper points to the Switch /
+    GShard form and prints no formula).  Reading taken:
+
+        f[e] = (number of tokens whose FIRST choice is e) / T     (before drops)
+        P[e] = mean over tokens of p[t,e]
+        L    = E * sum_e f[e] * P[e]
+
+    L = 1 for a perfectly uniform gate.  Returns (L, f, P)."""
+    p = np.asarray(p, _F)
+    T, E = p.shape
+    f = np.zeros(E, _F)
+    for t in range(T):
+        f[int(expert_idx[t, 0])] += 1.0
+    f /= T
+    P = p.sum(axis=0) / T
+    return float(E * np.dot(f, P)), f, P
+
+
+def aux_loss_bwd(p, f, coef):
+    """Gradient of coef * L with respect to the logits, f held constant (the
+    first-choice fractions are counts and carry no gradient):
+        dp[t,e] = coef * E * f[e] / T        for every token, dropped or not
+        dl[t,e] = p[t,e] (dp[t,e] - sum_e' p[t,e'] dp[t,e'])."""
+    p = np.asarray(p, _F)
+    T, E = p.shape
+    dp = np.broadcast_to(coef * E * np.asarray(f, _F) / T, (T, E))
+    return p * (dp - (p * dp).sum(axis=1, keepdims=True))
+
+
 def gate_logits_bwd(x, Wg, dlogits):
     """dWg = x^T dlogits;  dx_gate = dlogits Wg^T."""
     x = np.asarray(x, _F)
@@ -305,12 +339,14 @@ def gate_logits_bwd(x, Wg, dlogits):
 # --------------------------------------------------------------------------
 # the whole layer, forward and backward
 # --------------------------------------------------------------------------
-def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None):
+def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None, aux_coef=0.0):
     """One MoE layer forward and backward in the order gate -> capacity/RTS ->
     dispatch -> experts -> combine, then the reverse.  `logits`, when given,
     replaces the gate projection as the routing input (used to route on the
     fp32 logits another implementation produced); the gate projection's
-    backward still uses x and Wg.  Returns a dict of every intermediate."""
+    backward still uses x and Wg.  aux_coef > 0 adds aux_coef * (balancing loss)
+    to the objective: its value is returned and its gradient joins dlogits.
+    Returns a dict of every intermediate."""
     E = W1.shape[0]
     lg = gate_logits(x, Wg, bias) if logits is None else np.asarray(logits, _F)
     p = softmax(lg)
@@ -323,12 +359,16 @@ def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None):
     out = dict(logits=lg, probs=p, expert_idx=eidx, gate_w=g, slot=slot,
                expert_count=count, expert_demand=demand, slot_src=slot_src,
                Xd=Xd, Z=Z, H=H, Yd=Yd, y=y)
+    L, f, P = aux_loss(p, eidx)
+    out.update(aux_loss=L, first_frac=f, mean_prob=P)
     if dy is None:
         return out
     dYd, dg = combine_bwd(dy, Yd, eidx, slot, g)
     dXd, dW1, dW2 = expert_ffn_bwd(dYd, Xd, Z, count, W1, W2, kind)
     dx_disp = combine_fwd(dXd, eidx, slot, None)
     dl = gate_bwd(dg, p, eidx, slot)
+    if aux_coef != 0.0:
+        dl = dl + aux_loss_bwd(p, f, aux_coef)
     dWg, dx_gate = gate_logits_bwd(x, Wg, dl)
     out.update(dYd=dYd, dgate_w=dg, dXd=dXd, dW1=dW1, dW2=dW2, dx_disp=dx_disp,
                dlogits=dl, dWg=dWg, dx=dx_disp + dx_gate)
