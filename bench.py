@@ -48,6 +48,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--aux-coef", type=float, default=0.0,
+                    help="weight of the balancing auxiliary loss (Sec. 5.1 uses 0.01); 0 = the plain hot path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-call timings to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -99,9 +101,15 @@ def main():
         ("expert_ffn_bwd", lambda: B.moe_expert_ffn_bwd(s, L.dyd, L.xd, L.h, L.dact, L.expert_count, W1, W2,
                                                         L.dxd, L.dW1, L.dW2, L.ws)),
         ("dispatch_bwd", lambda: B.moe_combine_fwd(s, L.dxd, L.expert_idx, L.slot, None, L.dx)),
-        ("gate_bwd", lambda: B.moe_gate_bwd(s, L.dgate_w, L.probs, L.expert_idx, L.slot, L.dlogits)),
+        ("gate_bwd", (lambda: B.moe_gate_bwd(s, L.dgate_w, L.probs, L.expert_idx, L.slot, L.dlogits))
+         if args.aux_coef == 0.0 else
+         (lambda: B.moe_gate_bwd_aux(s, L.dgate_w, L.probs, L.expert_idx, L.slot, L.first_frac, args.aux_coef,
+                                     L.dlogits))),
         ("gate_logits_bwd", lambda: B.moe_gate_logits_bwd(s, x, Wg, L.dlogits, L.dWg, L.dx, L.ws)),
     ]
+    if args.aux_coef != 0.0:
+        calls.insert(2, ("aux_loss", lambda: B.moe_aux_loss(s, L.probs, L.expert_idx, L.first_frac, L.mean_prob,
+                                                            L.aux_loss, L.ws)))
     gemm_calls = {"expert_ffn_fwd", "expert_ffn_bwd"}
 
     for _ in range(args.warmup):
@@ -169,9 +177,12 @@ def main():
             "combine_bwd": Tn * dm * sb + M * dm * sb + M * dm * sb + 4 * Tn * k,
             "dispatch_bwd": M * dm * sb + 8 * Tn * k + Tn * dm * sb,
             "gate_bwd": Tn * E * 4 * 2 + 16 * Tn * k,
+            "aux_loss": Tn * E * 4 + 4 * Tn * k,
             "gate_logits_bwd": 2 * Tn * dm * sb + Tn * E * 4 + Tn * dm * sb + dm * E * 8,
         }
         for name, b in alg.items():
+            if name not in breakdown:
+                continue
             us = breakdown[name]["median_us"]
             breakdown[name]["alg_MB"] = b / 1e6
             breakdown[name]["GBps"] = b / (us * 1e-6) / 1e9
@@ -198,7 +209,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k,
                    "capacity": w.capacity, "capacity_factor": w.capacity_factor,
-                   "act": "gelu" if w.act == I.GELU else "relu", "kept_assignments": M,
+                   "act": "gelu" if w.act == I.GELU else "relu", "aux_coef": args.aux_coef, "kept_assignments": M,
                    "expert_demand_max": int(L.expert_demand.max().item()),
                    "expert_demand_min": int(L.expert_demand.min().item())},
         "roofline": roofline,

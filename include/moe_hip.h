@@ -162,6 +162,26 @@ int moe_expert_ffn_bwd(const moe_shape* shape, const void* dyd, const void* xd,
 int moe_gate_bwd(const moe_shape* shape, const float* dgate_w, const float* probs,
                  const int32_t* expert_idx, const int32_t* slot, float* dlogits, void* stream);
 
+/* Balancing auxiliary loss of the gate (Sec. 5.1, "MoE setting": an additional
+ * balancing loss, multiplied by 0.01, is added to the training loss; Switch /
+ * GShard form):
+ *   first_frac[E] f[e] = (tokens whose first choice expert_idx[t,0] is e) / T,
+ *                        counted before capacity drops
+ *   mean_prob[E]  P[e] = (1/T) sum_t probs[t,e]
+ *   loss[1]            = E * sum_e f[e] * P[e]         (1 for a uniform gate)
+ * All three outputs are device floats.  Needs workspace. */
+int moe_aux_loss(const moe_shape* shape, const float* probs, const int32_t* expert_idx,
+                 float* first_frac, float* mean_prob, float* loss, void* ws, size_t ws_bytes,
+                 void* stream);
+
+/* moe_gate_bwd plus the gradient of aux_coef * loss (f held constant, it is a
+ * count):  dp[t,e] gains aux_coef * E * first_frac[e] / T for EVERY token,
+ * dropped or not, before the softmax backward.  aux_coef is a host value
+ * (0.01 in Sec. 5.1, times any loss scale).  dlogits[T,E] is overwritten. */
+int moe_gate_bwd_aux(const moe_shape* shape, const float* dgate_w, const float* probs,
+                     const int32_t* expert_idx, const int32_t* slot, const float* first_frac,
+                     float aux_coef, float* dlogits, void* stream);
+
 /* Gate projection, backward:
  *   dWg[d_model,E]  = x^T * dlogits                       (overwritten)
  *   dx_accum[T,d]  += dlogits * Wg^T                      (ACCUMULATED into the

@@ -17,7 +17,7 @@ RELU, GELU = 0, 1
 EXPORTS = [
     "moe_status_string", "moe_capacity", "moe_workspace_bytes", "moe_gate_logits", "moe_gate_route",
     "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine_fwd", "moe_combine_bwd", "moe_expert_ffn_bwd",
-    "moe_gate_bwd", "moe_gate_logits_bwd",
+    "moe_gate_bwd", "moe_gate_logits_bwd", "moe_aux_loss", "moe_gate_bwd_aux",
 ]
 
 
@@ -61,6 +61,8 @@ def lib():
             "moe_expert_ffn_bwd": [shp] + [vp] * 11 + [sz, vp],
             "moe_gate_bwd": [shp] + [vp] * 6,
             "moe_gate_logits_bwd": [shp] + [vp] * 6 + [sz, vp],
+            "moe_aux_loss": [shp] + [vp] * 6 + [sz, vp],
+            "moe_gate_bwd_aux": [shp] + [vp] * 5 + [ctypes.c_float, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -149,6 +151,18 @@ def moe_expert_ffn_bwd(shape, dyd, xd, h_saved, dact_saved, expert_count, W1, W2
 def moe_gate_bwd(shape, dgate_w, probs, expert_idx, slot, dlogits, stream=None):
     _check(lib().moe_gate_bwd(ctypes.byref(shape), _p(dgate_w), _p(probs), _p(expert_idx), _p(slot),
                               _p(dlogits), _stream(stream)), "moe_gate_bwd")
+
+
+def moe_aux_loss(shape, probs, expert_idx, first_frac, mean_prob, loss, ws, stream=None):
+    _check(lib().moe_aux_loss(ctypes.byref(shape), _p(probs), _p(expert_idx), _p(first_frac), _p(mean_prob),
+                              _p(loss), _p(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                              _stream(stream)), "moe_aux_loss")
+
+
+def moe_gate_bwd_aux(shape, dgate_w, probs, expert_idx, slot, first_frac, aux_coef, dlogits, stream=None):
+    _check(lib().moe_gate_bwd_aux(ctypes.byref(shape), _p(dgate_w), _p(probs), _p(expert_idx), _p(slot),
+                                  _p(first_frac), float(aux_coef), _p(dlogits), _stream(stream)),
+           "moe_gate_bwd_aux")
 
 
 def moe_gate_logits_bwd(shape, x, Wg, dlogits, dWg, dx_accum, ws, stream=None):

@@ -28,5 +28,7 @@ extern "C" size_t moe_workspace_bytes(const moe_shape* shape) {
     const size_t b = ffn_bwd_ws_bytes(shape), c = gate_logits_bwd_ws_bytes(shape);
     if (b > n) n = b;
     if (c > n) n = c;
+    const size_t a = aux_loss_ws_bytes(shape);
+    if (a > n) n = a;
     return n;
 }

@@ -180,3 +180,4 @@ static inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE
 size_t route_ws_bytes(const moe_shape* s);
 size_t ffn_bwd_ws_bytes(const moe_shape* s);
 size_t gate_logits_bwd_ws_bytes(const moe_shape* s);
+size_t aux_loss_ws_bytes(const moe_shape* s);

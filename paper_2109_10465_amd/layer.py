@@ -12,13 +12,14 @@ _TORCH_DT = {B.F32: torch.float32, B.BF16: torch.bfloat16}
 
 
 class MoELayer:
-    def __init__(self, T, d_model, d_ff, E, k, capacity, dtype, act, device="cuda:0"):
+    def __init__(self, T, d_model, d_ff, E, k, capacity, dtype, act, device="cuda:0", aux_coef=0.0):
         if not torch.cuda.is_available():
             raise B.MoeError("MoELayer needs a GPU; there is no CPU fallback")
         B.lib()
         self.shape = B.make_shape(T, d_model, d_ff, E, k, capacity, dtype, act)
         self.T, self.d, self.f, self.E, self.k, self.C = T, d_model, d_ff, E, k, capacity
         self.device = torch.device(device)
+        self.aux_coef = float(aux_coef)     # weight of the balancing loss in the objective (0 = off)
         adt = _TORCH_DT[dtype]
         dev = self.device
 
@@ -34,6 +35,9 @@ class MoELayer:
         self.expert_count = buf((E,), i32)
         self.expert_demand = buf((E,), i32)
         self.slot_src = buf((E, capacity), i32)
+        self.first_frac = buf((E,), f32)     # balancing loss: first-choice share, mean probability, value
+        self.mean_prob = buf((E,), f32)
+        self.aux_loss = buf((1,), f32)
         self.xd = buf((E, capacity, d_model), adt)
         self.h = buf((E, capacity, d_ff), adt)       # act(z)
         self.dact = buf((E, capacity, d_ff), adt)    # act'(z)
@@ -64,6 +68,9 @@ class MoELayer:
             self.logits.copy_(logits)
         B.moe_gate_route(s, self.logits, rts_keys, self.probs, self.expert_idx, self.gate_w,
                          self.slot, self.expert_count, self.expert_demand, self.slot_src, self.ws)
+        if self.aux_coef != 0.0:
+            B.moe_aux_loss(s, self.probs, self.expert_idx, self.first_frac, self.mean_prob, self.aux_loss,
+                           self.ws)
         B.moe_dispatch(s, x, self.slot_src, self.expert_count, self.xd)
         B.moe_expert_ffn_fwd(s, self.xd, self.expert_count, W1, W2, self.h, self.dact, self.yd)
         B.moe_combine_fwd(s, self.yd, self.expert_idx, self.slot, self.gate_w, self.y)
@@ -78,7 +85,11 @@ class MoELayer:
                              self.dxd, self.dW1, self.dW2, self.ws)
         # dispatch's backward = combine with unit weights
         B.moe_combine_fwd(s, self.dxd, self.expert_idx, self.slot, None, self.dx)
-        B.moe_gate_bwd(s, self.dgate_w, self.probs, self.expert_idx, self.slot, self.dlogits)
+        if self.aux_coef != 0.0:
+            B.moe_gate_bwd_aux(s, self.dgate_w, self.probs, self.expert_idx, self.slot, self.first_frac,
+                               self.aux_coef, self.dlogits)
+        else:
+            B.moe_gate_bwd(s, self.dgate_w, self.probs, self.expert_idx, self.slot, self.dlogits)
         B.moe_gate_logits_bwd(s, x, Wg, self.dlogits, self.dWg, self.dx, self.ws)
         return self.dx, self.dWg, self.dW1, self.dW2
 

@@ -32,11 +32,11 @@ def rel_l2(got, want):
     return num / den if den > 0 else num
 
 
-def run_layer(w, d, use_keys=True, logits=None):
+def run_layer(w, d, use_keys=True, logits=None, aux_coef=0.0):
     """One forward+backward of workload w on the GPU; returns (layer, dict of
     host arrays) with the same names the oracle uses.  logits (fp32 numpy, made
     by the oracle) replaces the GPU's gate projection as the router's input."""
-    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act)
+    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act, aux_coef=aux_coef)
     x, dy = to_dev(d["x"], w.dtype), to_dev(d["dy"], w.dtype)
     W1, W2 = to_dev(d["W1"], w.dtype), to_dev(d["W2"], w.dtype)
     Wg = to_dev(d["Wg"], I.F32)
@@ -49,6 +49,8 @@ def run_layer(w, d, use_keys=True, logits=None):
     names = ["logits", "probs", "expert_idx", "gate_w", "slot", "expert_count", "expert_demand",
              "slot_src", "xd", "h", "dact", "yd", "y", "dyd", "dgate_w", "dxd", "dW1", "dW2",
              "dlogits", "dWg", "dx"]
+    if aux_coef != 0.0:
+        names += ["first_frac", "mean_prob", "aux_loss"]
     out = {n: host(getattr(layer, n)) for n in names}
     return layer, out
 
@@ -101,7 +103,7 @@ def row_mask(count, C):
     return np.arange(C)[None, :] < np.asarray(count)[:, None]
 
 
-def compare_full(w, d, got, ref):
+def compare_full(w, d, got, ref, aux=False):
     """Element-by-element comparison of every output of one GPU run with the
     oracle's: integers bit-exact, floats by rel-L2.  Returns the errors."""
     tol = TOL[w.dtype]
@@ -124,7 +126,8 @@ def compare_full(w, d, got, ref):
         assert errs[n] <= tol, (n, errs[n])
     dropped = np.all(ref["slot"] < 0, axis=1)
     assert not got["y"][dropped].any()
-    assert not got["dlogits"][dropped].any() and not got["dx"][dropped].any()
+    if not aux:     # the balancing loss reaches dropped tokens too
+        assert not got["dlogits"][dropped].any() and not got["dx"][dropped].any()
     return errs
 
 

@@ -22,7 +22,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = declared_symbols()
-    assert len(names) == 12
+    assert len(names) >= 14
     L = B.lib()
     for n in names:
         assert hasattr(L, n), n
