@@ -4,12 +4,17 @@
 //     f[e] = (tokens whose first choice is e) / T,   P[e] = mean_t p[t,e],
 //     L = E * sum_e f[e] * P[e].
 // All sums run in a fixed order (per-thread strided rows, then row groups, then
-// 256-token chunks), so the loss and its gradient are bit-reproducible.
+// chunks of tokens), so the loss and its gradient are bit-reproducible.
 #include "moe_common.h"
 
-#define AUX_CHUNK 256   // tokens per workgroup of the partial-sum kernel
-
-static inline int aux_chunks(const moe_shape* s) { return ceil_div(s->T, AUX_CHUNK); }
+// Tokens per workgroup of the partial-sum kernel: 64 for small batches (enough
+// workgroups to spread over the chip), more for large ones so that there are
+// never more than 1024 chunks.
+static inline int aux_chunk_tokens(const moe_shape* s) {
+    const int c = ceil_div(ceil_div(s->T, 1024), 64) * 64;
+    return c < 64 ? 64 : c;
+}
+static inline int aux_chunks(const moe_shape* s) { return ceil_div(s->T, aux_chunk_tokens(s)); }
 size_t aux_loss_ws_bytes(const moe_shape* s) {
     return align_up((size_t)aux_chunks(s) * s->E * 8, 256);   // float sums + int32 counts per chunk
 }
@@ -20,27 +25,37 @@ static inline int pow2_at_least(int v) {
     return p;
 }
 
-// Workgroup: one chunk of 256 tokens.  Thread (g, e) with e = tid % EP sums
-// column e over rows g, g+RS, g+2RS, ... of the chunk (EP = E rounded up to a
-// power of two, RS = 256 / EP row groups); the row groups are then added in
-// order.  First choices are counted with integer LDS atomics.
+// Workgroup: one chunk of tokens.  Thread (g, e) with e = tid % EP sums column e
+// over rows g, g+RS, g+2RS, ... of the chunk (EP = E rounded up to a power of
+// two, RS = 256 / EP row groups), 8 independent loads at a time; the row groups
+// are then added in order.  First choices are counted with integer LDS atomics.
 __global__ __launch_bounds__(256) void aux_partial_kernel(
-    int T, int E, int k, int EP, const float* __restrict__ probs,
+    int T, int E, int k, int EP, int chunk, const float* __restrict__ probs,
     const int32_t* __restrict__ expert_idx, float* __restrict__ part_sum, int32_t* __restrict__ part_cnt) {
     __shared__ float s_sum[256];
     __shared__ int32_t s_cnt[256];
     const int tid = threadIdx.x;
     const int e = tid & (EP - 1), g = tid / EP, RS = 256 / EP;
-    const int t0 = blockIdx.x * AUX_CHUNK;
-    const int rows = min(AUX_CHUNK, T - t0);
+    const int t0 = blockIdx.x * chunk;
+    const int rows = min(chunk, T - t0);
     s_cnt[tid] = 0;
     float acc = 0.0f;
-    if (e < E)
-        for (int r = g; r < rows; r += RS) acc += probs[(size_t)(t0 + r) * E + e];
+    if (e < E) {
+        for (int r0 = g; r0 < rows; r0 += 8 * RS) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = r0 + u * RS;
+                v[u] = r < rows ? probs[(size_t)(t0 + r) * E + e] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+    }
     s_sum[tid] = acc;
     __syncthreads();
-    if (tid < rows) {
-        const int e0 = expert_idx[(size_t)(t0 + tid) * k];
+    for (int r = tid; r < rows; r += 256) {
+        const int e0 = expert_idx[(size_t)(t0 + r) * k];
         if ((unsigned)e0 < (unsigned)E) atomicAdd(&s_cnt[e0], 1);   // ids outside [0,E) are not counted
     }
     __syncthreads();
@@ -52,28 +67,49 @@ __global__ __launch_bounds__(256) void aux_partial_kernel(
     }
 }
 
-// One workgroup: thread e adds the chunk partials of expert e in chunk order.
+// One workgroup: thread (g, e) adds the partials of chunks g, g+RS, ... of expert
+// e (8 independent loads at a time); the groups are then added in order.
 __global__ __launch_bounds__(256) void aux_final_kernel(
-    int T, int E, int nchunk, const float* __restrict__ part_sum, const int32_t* __restrict__ part_cnt,
-    float* __restrict__ first_frac, float* __restrict__ mean_prob, float* __restrict__ loss) {
+    int T, int E, int EP, int nchunk, const float* __restrict__ part_sum,
+    const int32_t* __restrict__ part_cnt, float* __restrict__ first_frac, float* __restrict__ mean_prob,
+    float* __restrict__ loss) {
+    __shared__ float s_sum[256];
+    __shared__ int32_t s_cnt[256];
     __shared__ float s_prod[256];
-    const int e = threadIdx.x;
-    float prod = 0.0f;
+    const int tid = threadIdx.x;
+    const int e = tid & (EP - 1), g = tid / EP, RS = 256 / EP;
+    float acc = 0.0f;
+    int cnt = 0;
     if (e < E) {
+        for (int q0 = g; q0 < nchunk; q0 += 8 * RS) {
+            float v[8];
+            int c[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int q = q0 + u * RS;
+                v[u] = q < nchunk ? part_sum[(size_t)q * E + e] : 0.0f;
+                c[u] = q < nchunk ? part_cnt[(size_t)q * E + e] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { acc += v[u]; cnt += c[u]; }
+        }
+    }
+    s_sum[tid] = acc;
+    s_cnt[tid] = cnt;
+    __syncthreads();
+    float prod = 0.0f;
+    if (tid < E) {
         float s = 0.0f;
         int c = 0;
-        for (int q = 0; q < nchunk; ++q) {
-            s += part_sum[(size_t)q * E + e];
-            c += part_cnt[(size_t)q * E + e];
-        }
+        for (int q = 0; q < RS; ++q) { s += s_sum[q * EP + tid]; c += s_cnt[q * EP + tid]; }
         const float f = (float)c / (float)T, P = s / (float)T;
-        first_frac[e] = f;
-        mean_prob[e] = P;
+        first_frac[tid] = f;
+        mean_prob[tid] = P;
         prod = f * P;
     }
-    s_prod[e] = prod;
+    s_prod[tid] = prod;
     __syncthreads();
-    if (e == 0) {
+    if (tid == 0) {
         float L = 0.0f;
         for (int q = 0; q < E; ++q) L += s_prod[q];
         loss[0] = (float)E * L;
@@ -91,10 +127,11 @@ extern "C" int moe_aux_loss(const moe_shape* shape, const float* probs, const in
     const int nchunk = aux_chunks(shape);
     float* part_sum = (float*)ws;
     int32_t* part_cnt = (int32_t*)(part_sum + (size_t)nchunk * shape->E);
-    aux_partial_kernel<<<nchunk, 256, 0, st>>>(shape->T, shape->E, shape->k, pow2_at_least(shape->E), probs,
+    const int EP = pow2_at_least(shape->E);
+    aux_partial_kernel<<<nchunk, 256, 0, st>>>(shape->T, shape->E, shape->k, EP, aux_chunk_tokens(shape), probs,
                                                expert_idx, part_sum, part_cnt);
-    aux_final_kernel<<<1, 256, 0, st>>>(shape->T, shape->E, nchunk, part_sum, part_cnt, first_frac, mean_prob,
-                                        loss);
+    aux_final_kernel<<<1, 256, 0, st>>>(shape->T, shape->E, EP, nchunk, part_sum, part_cnt, first_frac,
+                                        mean_prob, loss);
     return launch_status();
 }
 
