@@ -22,7 +22,7 @@ PEAK_F32_MFMA = 157.3e12     # fp32 matrix
 PEAK_HBM = 8.0e12            # B/s
 
 
-def cpu_baseline(w, d, budget_flops=2.0e12):
+def cpu_baseline(w, d, budget_flops=2.0e12, forward_only=False):
     """The CPU oracle, as it stands, on a bounded sample of the same workload:
     the first Ts tokens (all of them if the whole layer is below ~2e12 flop),
     capacity scaled with Ts.  Timed on this host's cores."""
@@ -33,12 +33,13 @@ def cpu_baseline(w, d, budget_flops=2.0e12):
     Ts = w.T if full <= budget_flops else max(w.E * 8, int(w.T * budget_flops / full))
     C = w.capacity if Ts == w.T else O.capacity(Ts, w.E, w.k, w.capacity_factor)
     t0 = time.time()
-    O.moe_layer(d["x"][:Ts], d["Wg"], d["bias"], d["W1"], d["W2"], d["rts_keys"][:Ts], d["dy"][:Ts],
-                w.k, C, w.act)
+    O.moe_layer(d["x"][:Ts], d["Wg"], d["bias"], d["W1"], d["W2"], d["rts_keys"][:Ts],
+                None if forward_only else d["dy"][:Ts], w.k, C, w.act)
     dt = time.time() - t0
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     return {"value": Ts / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"first {Ts} of {w.T} tokens, all {w.E} experts, capacity {C}, fwd+bwd in fp64, "
+            "sample": f"first {Ts} of {w.T} tokens, all {w.E} experts, capacity {C}, "
+                      f"{'fwd' if forward_only else 'fwd+bwd'} in fp64, "
                       f"{dt:.1f} s on {os.cpu_count()} visible cpus"}
 
 
@@ -50,6 +51,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--aux-coef", type=float, default=0.0,
                     help="weight of the balancing auxiliary loss (Sec. 5.1 uses 0.01); 0 = the plain hot path")
+    ap.add_argument("--forward-only", action="store_true",
+                    help="evaluation path: forward only, capacity factor 2.0, utilisation counting (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-call timings to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -78,6 +81,9 @@ def main():
         return
     B.lib()
     w = I.WORKLOADS[args.workload]
+    if args.forward_only:
+        import dataclasses
+        w = dataclasses.replace(w, capacity=B.moe_capacity(w.T, w.E, w.k, 2.0), capacity_factor=2.0)
     d = I.make_inputs(w, seed=0)
     adt = torch.bfloat16 if w.dtype == I.BF16 else torch.float32
 
@@ -86,7 +92,7 @@ def main():
 
     x, dy, W1, W2 = dev(d["x"], adt), dev(d["dy"], adt), dev(d["W1"], adt), dev(d["W2"], adt)
     Wg, bias, keys = dev(d["Wg"]), dev(d["bias"]), dev(d["rts_keys"])
-    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act)
+    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act, forward_only=args.forward_only)
     s = layer.shape
     L = layer
 
@@ -107,9 +113,12 @@ def main():
                                      L.dlogits))),
         ("gate_logits_bwd", lambda: B.moe_gate_logits_bwd(s, x, Wg, L.dlogits, L.dWg, L.dx, L.ws)),
     ]
-    if args.aux_coef != 0.0:
+    if args.aux_coef != 0.0 and not args.forward_only:
         calls.insert(2, ("aux_loss", lambda: B.moe_aux_loss(s, L.probs, L.expert_idx, L.first_frac, L.mean_prob,
                                                             L.aux_loss, L.ws)))
+    if args.forward_only:
+        calls = calls[:[n for n, _ in calls].index("combine_fwd") + 1]
+        calls.insert(2, ("utilisation", lambda: B.moe_utilisation_accumulate(s, L.expert_demand, L.utilisation)))
     gemm_calls = {"expert_ffn_fwd", "expert_ffn_bwd"}
 
     for _ in range(args.warmup):
@@ -119,7 +128,8 @@ def main():
 
     # timed region: exactly K steps; HIP events (torch's current stream is the
     # stream the kernels are launched on) bracket the expert-GEMM calls
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    n_gemm_calls = sum(1 for n, _ in calls if n in gemm_calls)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * n_gemm_calls)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -134,10 +144,11 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    gemm_ms = sum(a.elapsed_time(b) + c.elapsed_time(dd) for a, b, c, dd in ev) / args.steps
+    gemm_ms = sum(sum(e[2 * i].elapsed_time(e[2 * i + 1]) for i in range(n_gemm_calls)) for e in ev) / args.steps
 
     M = int(L.expert_count.sum().item())                      # kept assignments actually routed
-    flops = 12.0 * M * w.d_model * w.d_ff                     # 6 grouped GEMMs, 2*M*d*f each
+    n_gemm = 2 if args.forward_only else 6
+    flops = 2.0 * n_gemm * M * w.d_model * w.d_ff             # grouped GEMMs of 2*M*d*f each
     peak = PEAK_BF16_MFMA if w.dtype == I.BF16 else PEAK_F32_MFMA
     achieved = flops / (gemm_ms * 1e-3)
     traffic = None
@@ -146,10 +157,10 @@ def main():
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = float(line.split("=")[1])
-    roofline = {"bound": "mfma", "kernel": "grouped_gemm_kernel (6 launches per step)",
+    roofline = {"bound": "mfma", "kernel": f"grouped_gemm_kernel ({n_gemm} launches per step)",
                 "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
                 "frac": achieved / peak, "traffic": traffic,
-                "flops_per_launch": flops / 6.0, "avg_launch_ms": gemm_ms / 6.0,
+                "flops_per_launch": flops / n_gemm, "avg_launch_ms": gemm_ms / n_gemm,
                 "kept_assignments": M}
 
     breakdown = None
@@ -188,6 +199,8 @@ def main():
             breakdown[name]["GBps"] = b / (us * 1e-6) / 1e9
             breakdown[name]["hbm_frac"] = b / (us * 1e-6) / PEAK_HBM
         for name, fl in (("expert_ffn_fwd", 4.0), ("expert_ffn_bwd", 8.0)):
+            if name not in breakdown:
+                continue
             us = breakdown[name]["median_us"]
             breakdown[name]["TFLOPs"] = fl * M * dm * w.d_ff / (us * 1e-6) / 1e12
             breakdown[name]["mfma_frac"] = fl * M * dm * w.d_ff / (us * 1e-6) / peak
@@ -209,7 +222,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k,
                    "capacity": w.capacity, "capacity_factor": w.capacity_factor,
-                   "act": "gelu" if w.act == I.GELU else "relu", "aux_coef": args.aux_coef, "kept_assignments": M,
+                   "act": "gelu" if w.act == I.GELU else "relu", "aux_coef": args.aux_coef,
+                   "mode": "forward-only (evaluation)" if args.forward_only else "forward+backward (training)",
+                   "kept_assignments": M,
                    "expert_demand_max": int(L.expert_demand.max().item()),
                    "expert_demand_min": int(L.expert_demand.min().item())},
         "roofline": roofline,
@@ -219,7 +234,7 @@ def main():
     if not args.no_cpu_baseline:
         del x, dy, W1, W2, layer, L
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(w, d)
+        out["cpu_baseline"] = cpu_baseline(w, d, forward_only=args.forward_only)
     print(json.dumps(out), flush=True)
 
 

@@ -124,10 +124,22 @@ int moe_dispatch(const moe_shape* shape, const void* x, const int32_t* slot_src,
  *   yd_e = h * W2_e      (W2[E,d_ff,d_model])      -> yd[E,C,d_model]
  * No biases.  relu'(z) = [z > 0]; gelu'(z) = Phi(z) + z phi(z).  h_saved and
  * dact_saved are kept by the caller for the backward: the activation and its
- * derivative are both evaluated here, once, while z is in registers. */
+ * derivative are both evaluated here, once, while z is in registers.
+ * Forward-only use (evaluation, Sec. 5.1: capacity factor 2.0): pass
+ * dact_saved = NULL and the derivative is neither computed nor written;
+ * h_saved is still required (it is the second matmul's input). */
 int moe_expert_ffn_fwd(const moe_shape* shape, const void* xd, const int32_t* expert_count,
                        const void* W1, const void* W2, void* h_saved, void* dact_saved, void* yd,
                        void* stream);
+
+/* Expert utilisation for pruning (Sec. 3.3: the experts with the highest
+ * utilisation are kept; utilisation = number of times a token is routed to
+ * the expert over a validation set):  accum[e] += counts[e] for e < E, with
+ * counts = expert_demand (every routed candidate) or expert_count (kept ones)
+ * of the batch just routed.  accum[E] is int64 and is owned, and zeroed before
+ * the first batch, by the caller. */
+int moe_utilisation_accumulate(const moe_shape* shape, const int32_t* counts, int64_t* accum,
+                               void* stream);
 
 /* Combine (the mixture itself; a token dropped by every chosen expert gets a
  * zero row and is carried by the residual connection around the layer,

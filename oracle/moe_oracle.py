@@ -329,6 +329,17 @@ def aux_loss_bwd(p, f, coef):
     return p * (dp - (p * dp).sum(axis=1, keepdims=True))
 
 
+def utilisation(expert_idx_batches, E):
+    """Pruning statistic (Sec. 3.3): the number of times a token is routed to
+    each expert over a set of batches, counted on the gate's choices (every
+    routed candidate, first and second choices alike, dropped or not)."""
+    u = np.zeros(E, np.int64)
+    for eidx in expert_idx_batches:
+        for e in np.asarray(eidx).ravel():
+            u[int(e)] += 1
+    return u
+
+
 def gate_logits_bwd(x, Wg, dlogits):
     """dWg = x^T dlogits;  dx_gate = dlogits Wg^T."""
     x = np.asarray(x, _F)

@@ -18,6 +18,7 @@ EXPORTS = [
     "moe_status_string", "moe_capacity", "moe_workspace_bytes", "moe_gate_logits", "moe_gate_route",
     "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine_fwd", "moe_combine_bwd", "moe_expert_ffn_bwd",
     "moe_gate_bwd", "moe_gate_logits_bwd", "moe_aux_loss", "moe_gate_bwd_aux",
+    "moe_utilisation_accumulate",
 ]
 
 
@@ -63,6 +64,7 @@ def lib():
             "moe_gate_logits_bwd": [shp] + [vp] * 6 + [sz, vp],
             "moe_aux_loss": [shp] + [vp] * 6 + [sz, vp],
             "moe_gate_bwd_aux": [shp] + [vp] * 5 + [ctypes.c_float, vp, vp],
+            "moe_utilisation_accumulate": [shp, vp, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -163,6 +165,11 @@ def moe_gate_bwd_aux(shape, dgate_w, probs, expert_idx, slot, first_frac, aux_co
     _check(lib().moe_gate_bwd_aux(ctypes.byref(shape), _p(dgate_w), _p(probs), _p(expert_idx), _p(slot),
                                   _p(first_frac), float(aux_coef), _p(dlogits), _stream(stream)),
            "moe_gate_bwd_aux")
+
+
+def moe_utilisation_accumulate(shape, counts, accum, stream=None):
+    _check(lib().moe_utilisation_accumulate(ctypes.byref(shape), _p(counts), _p(accum), _stream(stream)),
+           "moe_utilisation_accumulate")
 
 
 def moe_gate_logits_bwd(shape, x, Wg, dlogits, dWg, dx_accum, ws, stream=None):

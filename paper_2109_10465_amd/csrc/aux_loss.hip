@@ -230,3 +230,22 @@ extern "C" int moe_gate_bwd_aux(const moe_shape* shape, const float* dgate_w, co
 #undef GBA
     return launch_status();
 }
+
+// ---------------------------------------------------------------------------
+// Expert utilisation (Sec. 3.3: experts are ranked for pruning by how many
+// tokens were routed to each of them over a validation set).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void utilisation_kernel(int E, const int32_t* __restrict__ counts,
+                                                          long long* __restrict__ accum) {
+    const int e = threadIdx.x;
+    if (e < E) accum[e] += (long long)counts[e];
+}
+
+extern "C" int moe_utilisation_accumulate(const moe_shape* shape, const int32_t* counts,
+                                          int64_t* accum, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!counts || !accum) return MOE_ERR_NULL;
+    utilisation_kernel<<<1, 256, 0, (hipStream_t)stream>>>(shape->E, counts, (long long*)accum);
+    return launch_status();
+}

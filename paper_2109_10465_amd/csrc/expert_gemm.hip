@@ -59,7 +59,7 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) s16x4_t lds_s16x4_t;
 
-enum { EPI_STORE = 0, EPI_H_DACT = 1, EPI_MUL = 2, EPI_F32 = 3 };
+enum { EPI_STORE = 0, EPI_H_DACT = 1, EPI_MUL = 2, EPI_F32 = 3, EPI_H = 4 };   // EPI_H: activation only (forward-only use)
 
 struct GemmArgs {
     const void* A; const void* B;
@@ -69,7 +69,7 @@ struct GemmArgs {
     int lda, ldb, ldo;
     int M, N, K;      // extents; the one bounded by expert_count is an upper limit
     int var_k;        // 0: rows (M) bounded by expert_count; 1: K bounded by it
-    int tiles_m, tiles_n, total_tiles, tiles_per_xcd;
+    int tiles_m, tiles_n, E;
 };
 
 template <typename T> struct Mma;
@@ -264,6 +264,11 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& p, size_t o, float (&v
         for (int i = 0; i < 4; ++i) act_both<sizeof(T) == 2, ACT>(v[i], h[i], a[i]);
         *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(a);
         *reinterpret_cast<raw*>((T*)p.out1 + o) = Vec4io<T>::pack(h);
+    } else if constexpr (EPI == EPI_H) {
+        float h[4], a[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) act_both<sizeof(T) == 2, ACT>(v[i], h[i], a[i]);   // the derivative is dead code here
+        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(h);
     } else if constexpr (EPI == EPI_MUL) {
         float a[4];
         Vec4io<T>::unpack(aux, a);
@@ -295,42 +300,88 @@ struct GemmSmem {
     static constexpr int LOADS = TA::PER_THREAD + TB::PER_THREAD;  // per thread per slab
     static_assert(NSTAGE * LOADS < 64, "vmcnt is a 6-bit counter");
     static_assert((BK / Mma<T>::KSTEP) % 2 == 0, "fragment double buffering needs an even number of k-steps");
-    static_assert(BYTES <= 160 * 1024, "LDS of one CU");
+    static_assert(BYTES + 4096 <= 160 * 1024, "LDS of one CU (the tile-walk table follows)");
 };
 
-// The walk of one workgroup over its tiles.  Workgroup w serves XCD w % 8 (ids
-// are dealt round-robin to the XCDs) and takes every (gridDim/8)-th tile of that
-// XCD's contiguous run of logical tiles (= whole experts), so the ~32 tiles an
-// XCD works on at once share operand panels in its L2.  Tiles beyond an
-// expert's rows are skipped.
+// The walk of one workgroup over its tiles.  Only tiles that hold rows exist:
+// expert e has ceil(n_e / BM) row tiles (all of them if the expert count is the
+// reduction length: an empty expert's weight gradient is still written, as zeros).
+// A table in LDS holds the running number of tiles per expert.  The tile
+// sequence (expert-major) is dealt block-cyclically: with S workgroups per XCD
+// (workgroup w serves XCD w % 8: ids are dealt round-robin to the XCDs), block b
+// of S consecutive tiles goes to XCD b % 8, one tile per workgroup.  The tiles an
+// XCD works on at one time are neighbours and share operand panels in its L2;
+// every workgroup gets the same number of tiles up to one; and the tiles of a
+// heavily loaded expert (long reductions in the weight-gradient GEMMs) are spread
+// over all workgroups instead of piling up on one XCD.
+#define WALK_SLOTS 257                  // experts + 1
+#define WALK_BYTES (WALK_SLOTS * 4 + 12)
 template <int BM, int BN>
 struct TileWalk {
-    int logical, end, step;
+    const int* tp;          // LDS: tiles before expert e (tp[256] = all tiles)
+    int t, t_end, step;
     int e, m0, n0, m_lim, k_lim;   // current tile
-    __device__ __forceinline__ void start(const GemmArgs& p) {
-        const int xcd = blockIdx.x & 7;
-        step = gridDim.x >> 3;
-        logical = xcd * p.tiles_per_xcd + (blockIdx.x >> 3) - step;
-        end = min((xcd + 1) * p.tiles_per_xcd, p.total_tiles);
-    }
-    // moves to the next non-empty tile; false when the walk is over
-    __device__ __forceinline__ bool next(const GemmArgs& p) {
-        const int per_e = p.tiles_m * p.tiles_n;
-        for (;;) {
-            logical += step;
-            if (logical >= end) return false;
-            e = logical / per_e;
-            const int rem = logical - e * per_e;
-            // inside an expert the dimension with fewer tiles varies fastest
-            int tm, tn;
-            if (p.tiles_m <= p.tiles_n) { tn = rem / p.tiles_m; tm = rem - tn * p.tiles_m; }
-            else { tm = rem / p.tiles_n; tn = rem - tm * p.tiles_n; }
-            const int n_e = p.expert_count[e];
-            m0 = tm * BM; n0 = tn * BN;
-            m_lim = p.var_k ? p.M : n_e;
-            k_lim = p.var_k ? n_e : p.K;
-            if (m0 < m_lim) return true;
+
+    // Fills the table (wave 0; 4 experts per lane) and synchronises the workgroup.
+    __device__ static __forceinline__ void build(const GemmArgs& p, unsigned char* lds) {
+        int* tpw = reinterpret_cast<int*>(lds);
+        if (threadIdx.x < 64) {
+            const int lane = threadIdx.x;
+            int a[4];
+            int sa = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int ex = 4 * lane + i;
+                int n = ex < p.E ? p.expert_count[ex] : 0;
+                n = max(0, min(n, p.var_k ? p.K : p.M));
+                const int tm = ex >= p.E ? 0 : (p.var_k ? p.tiles_m : (n + BM - 1) / BM);
+                a[i] = tm * p.tiles_n;
+                sa += a[i];
+            }
+            int ia = sa;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int va = __shfl_up(ia, o, MOE_WAVE);
+                if (lane >= o) ia += va;
+            }
+            int ea = ia - sa;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                tpw[4 * lane + i] = ea;
+                ea += a[i];
+            }
+            if (lane == 63) tpw[256] = ea;
         }
+        __syncthreads();
+    }
+    __device__ __forceinline__ void start(const GemmArgs& p, const unsigned char* lds) {
+        tp = reinterpret_cast<const int*>(lds);
+        const int S = gridDim.x >> 3;
+        step = 8 * S;
+        t = (int)(blockIdx.x & 7) * S + (int)(blockIdx.x >> 3) - step;
+        t_end = __builtin_amdgcn_readfirstlane(tp[256]);
+        e = 0;
+    }
+    // moves to the workgroup's next tile; false when the walk is over
+    __device__ __forceinline__ bool next(const GemmArgs& p) {
+        t += step;
+        if (t >= t_end) return false;
+        while (t >= tp[e + 1]) ++e;          // t < tp[256]: stops at an expert that has tiles
+        // everything here is the same in every lane; keep it in scalar registers
+        e = __builtin_amdgcn_readfirstlane(e);
+        const int first = __builtin_amdgcn_readfirstlane(tp[e]);
+        const int count = __builtin_amdgcn_readfirstlane(tp[e + 1]) - first;
+        const int rem = t - first;
+        const int tm_e = count / p.tiles_n;   // row tiles of this expert
+        // inside an expert the dimension with fewer tiles varies fastest
+        int tm, tn;
+        if (tm_e <= p.tiles_n) { tn = rem / tm_e; tm = rem - tn * tm_e; }
+        else { tm = rem / p.tiles_n; tn = rem - tm * p.tiles_n; }
+        const int n_e = max(0, min(p.expert_count[e], p.var_k ? p.K : p.M));
+        m0 = tm * BM; n0 = tn * BN;
+        m_lim = p.var_k ? p.M : n_e;
+        k_lim = p.var_k ? n_e : p.K;
+        return true;
     }
 };
 
@@ -366,8 +417,10 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
     float* strip = reinterpret_cast<float*>(smem_raw + SM::RING) + wave * SM::EPI_ROWS * ELD;
 
     // ---- producer: the stream of slabs of all tiles of this workgroup ---------
-    TileWalk<BM, BN> pw;           // tile whose slabs are being requested
-    pw.start(p);
+    unsigned char* walk_lds = smem_raw + SM::BYTES;
+    TileWalk<BM, BN>::build(p, walk_lds);
+    TileWalk<BM, BN> pw;       // tile whose slabs are being requested
+    pw.start(p, walk_lds);
     bool p_more = pw.next(p);
     int p_kt = 0, p_nk = 0;
     u32x4_t dsA = {0, 0, 0, 0}, dsB = {0, 0, 0, 0};
@@ -411,7 +464,7 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
 #endif
     // ---- consumer ---------------------------------------------------------------
     TileWalk<BM, BN> cw;
-    cw.start(p);
+    cw.start(p, walk_lds);
     if (!cw.next(p)) return;       // nothing to do for this workgroup (uniform)
 #pragma unroll
     for (int s = 0; s < NS; ++s) produce(s);
@@ -521,7 +574,7 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                     for (int r = 0; r < 4; ++r)
                         strip[(4 * g + r) * ELD + j * 32 + l32] = acc[i][j][4 * q + r];
                 const int m_strip = mrow + i * 32 + q * 8;
-                if constexpr (EPI == EPI_H_DACT) {
+                if constexpr (EPI == EPI_H_DACT || EPI == EPI_H) {
 #pragma unroll 1
                     for (int it = 0; it < NIT; ++it) {  // rolled: one copy of the activation code per strip
                         const float4 w = *reinterpret_cast<const float4*>(strip + (er + it * RPI) * ELD + ec);
@@ -582,14 +635,15 @@ static void launch_gemm(GemmArgs p, int E, hipStream_t st) {
     typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC, NWN> SM;
     p.tiles_m = ceil_div(p.M, BM);
     p.tiles_n = ceil_div(p.N, BN);
-    p.total_tiles = E * p.tiles_m * p.tiles_n;
-    p.tiles_per_xcd = ceil_div(p.total_tiles, 8);
+    p.E = E;
     // one persistent workgroup per CU (its LDS footprint allows no second one),
-    // in groups of 8 so that every XCD gets the same number
+    // in groups of 8 so that every XCD gets the same number; never more than
+    // there could be tiles
+    const long long most = ((long long)E * p.tiles_m * p.tiles_n + 7) / 8;
     int per_xcd = num_cus() / 8;
     if (per_xcd < 1) per_xcd = 1;
-    if (per_xcd > p.tiles_per_xcd) per_xcd = p.tiles_per_xcd;
-    const size_t smem = SM::BYTES;
+    if (per_xcd > most) per_xcd = (int)most;
+    const size_t smem = SM::BYTES + WALK_BYTES;
     auto kern = grouped_gemm_kernel<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN>;
     if (smem > 64 * 1024) {
         // opt in (once per kernel instance) to more than 64 KB of the CU's 160 KB LDS
@@ -623,7 +677,11 @@ static void ffn_fwd(const moe_shape* s, const void* xd, const int32_t* cnt, cons
     p.B = W1; p.ldb = f; p.strideB = (long long)d * f;
     p.out0 = a; p.out1 = h; p.ldo = f; p.strideO = (long long)C * f;
     p.M = C; p.N = f; p.K = d;
-    if (s->act == MOE_RELU) launch_gemm<T, BM, BN, BK, true, false, EPI_H_DACT, MOE_RELU>(p, E, st);
+    if (!a) {   // forward-only: the derivative is neither computed nor stored
+        p.out0 = h; p.out1 = nullptr;
+        if (s->act == MOE_RELU) launch_gemm<T, BM, BN, BK, true, false, EPI_H, MOE_RELU>(p, E, st);
+        else launch_gemm<T, BM, BN, BK, true, false, EPI_H, MOE_GELU>(p, E, st);
+    } else if (s->act == MOE_RELU) launch_gemm<T, BM, BN, BK, true, false, EPI_H_DACT, MOE_RELU>(p, E, st);
     else launch_gemm<T, BM, BN, BK, true, false, EPI_H_DACT, MOE_GELU>(p, E, st);
     // yd = h W2
     p.A = h; p.lda = f; p.strideA = (long long)C * f;
@@ -674,7 +732,7 @@ extern "C" int moe_expert_ffn_fwd(const moe_shape* shape, const void* xd,
     int rc = check_shape(shape);
     if (rc) return rc;
     if ((rc = check_slice_limits(shape))) return rc;
-    if (!xd || !expert_count || !W1 || !W2 || !h_saved || !dact_saved || !yd) return MOE_ERR_NULL;
+    if (!xd || !expert_count || !W1 || !W2 || !h_saved || !yd) return MOE_ERR_NULL;   // dact_saved may be NULL
     hipStream_t st = (hipStream_t)stream;
     if (shape->dtype == MOE_BF16)
         ffn_fwd<bf16_t, MOE_GEMM_BM, MOE_GEMM_BN, MOE_GEMM_BK>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, st);

@@ -12,7 +12,8 @@ _TORCH_DT = {B.F32: torch.float32, B.BF16: torch.bfloat16}
 
 
 class MoELayer:
-    def __init__(self, T, d_model, d_ff, E, k, capacity, dtype, act, device="cuda:0", aux_coef=0.0):
+    def __init__(self, T, d_model, d_ff, E, k, capacity, dtype, act, device="cuda:0", aux_coef=0.0,
+                 forward_only=False):
         if not torch.cuda.is_available():
             raise B.MoeError("MoELayer needs a GPU; there is no CPU fallback")
         B.lib()
@@ -20,6 +21,7 @@ class MoELayer:
         self.T, self.d, self.f, self.E, self.k, self.C = T, d_model, d_ff, E, k, capacity
         self.device = torch.device(device)
         self.aux_coef = float(aux_coef)     # weight of the balancing loss in the objective (0 = off)
+        self.forward_only = bool(forward_only)   # evaluation: no saved derivative, no backward buffers
         adt = _TORCH_DT[dtype]
         dev = self.device
 
@@ -40,9 +42,16 @@ class MoELayer:
         self.aux_loss = buf((1,), f32)
         self.xd = buf((E, capacity, d_model), adt)
         self.h = buf((E, capacity, d_ff), adt)       # act(z)
-        self.dact = buf((E, capacity, d_ff), adt)    # act'(z)
+        self.dact = None if forward_only else buf((E, capacity, d_ff), adt)    # act'(z)
         self.yd = buf((E, capacity, d_model), adt)
         self.y = buf((T, d_model), adt)
+        self.utilisation = torch.zeros((E,), dtype=torch.int64, device=dev)   # tokens routed to each expert so far
+        nbytes = B.moe_workspace_bytes(self.shape)
+        if nbytes == 0:
+            raise B.MoeError("unsupported shape")
+        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        if forward_only:
+            return
         # backward
         self.dyd = buf((E, capacity, d_model), adt)
         self.dgate_w = buf((T, k), f32)
@@ -52,10 +61,6 @@ class MoELayer:
         self.dlogits = buf((T, E), f32)
         self.dWg = buf((d_model, E), f32)
         self.dx = buf((T, d_model), adt)
-        nbytes = B.moe_workspace_bytes(self.shape)
-        if nbytes == 0:
-            raise B.MoeError("unsupported shape")
-        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
 
     def forward(self, x, Wg, bias, W1, W2, rts_keys, logits=None):
         """logits: optional precomputed [T,E] fp32 gate logits; the projection call is
@@ -68,6 +73,8 @@ class MoELayer:
             self.logits.copy_(logits)
         B.moe_gate_route(s, self.logits, rts_keys, self.probs, self.expert_idx, self.gate_w,
                          self.slot, self.expert_count, self.expert_demand, self.slot_src, self.ws)
+        if self.forward_only:
+            B.moe_utilisation_accumulate(s, self.expert_demand, self.utilisation)
         if self.aux_coef != 0.0:
             B.moe_aux_loss(s, self.probs, self.expert_idx, self.first_frac, self.mean_prob, self.aux_loss,
                            self.ws)
@@ -77,6 +84,8 @@ class MoELayer:
         return self.y
 
     def backward(self, dy):
+        if self.forward_only:
+            raise B.MoeError("this layer was built forward-only")
         s = self.shape
         x, Wg, W1, W2 = self._saved
         B.moe_combine_bwd(s, dy, self.yd, self.expert_idx, self.slot, self.gate_w, self.dyd,

@@ -182,3 +182,21 @@ def test_rts_keep_rate_is_flat_in_position_and_plain_priority_is_a_step():
     kept, cand = _keep_by_decile(False, range(5))
     r = kept / cand
     assert np.all(r[:3] == 1.0) and np.all(r[4:] == 0.0)       # prefix kept, suffix dropped
+
+
+def test_utilisation_counts_every_routed_candidate_and_sums_the_demands():
+    """Sec. 3.3 pruning statistic: over several batches the count per expert is
+    the sum of the per-batch demands (a bincount of the choices), whatever the
+    capacity dropped."""
+    rng = np.random.default_rng(9)
+    E, batches, demands = 6, [], []
+    for T in (50, 1, 77):
+        lg = rng.standard_normal((T, E))
+        eidx = O.top_k(lg, 2)
+        _, _, demand, _ = O.route(eidx, rng.random(T), E, 5)     # tight capacity: many drops
+        batches.append(eidx); demands.append(demand)
+    u = O.utilisation(batches, E)
+    assert u.dtype == np.int64 and u.sum() == 2 * (50 + 1 + 77)
+    assert np.array_equal(u, np.sum(demands, axis=0))
+    assert np.array_equal(u, np.bincount(np.concatenate([b.ravel() for b in batches]), minlength=E))
+    assert np.array_equal(O.utilisation([], E), np.zeros(E, np.int64))
