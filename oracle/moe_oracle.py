@@ -149,6 +149,40 @@ def route(expert_idx, rts_keys, E, C):
     return slot, count, demand, slot_src
 
 
+def route_grouped(expert_idx, rts_keys, E, C, G):
+    """Grouped token selection (Sec. 3.1: a group dimension batches consecutive
+    sentences, and the selection happens inside each group; Sec. 5.5 compares
+    plain, grouped and RTS selection).
+
+    The T tokens form G groups of T/G consecutive tokens.  Each group routes on
+    its own with the rule of route() and C/G slots per expert, so the bias
+    towards early positions is confined to a group.  An expert's kept rows of
+    group 0 come first in its buffer, then those of group 1, and so on, with no
+    gaps: slot = (rows kept for this expert in earlier groups) + rank in group.
+
+    Returns slot[T,k], expert_count[E], expert_demand[E], slot_src[E,C]."""
+    expert_idx = np.asarray(expert_idx)
+    T, k = expert_idx.shape
+    assert T % G == 0 and C % G == 0
+    Tg, Cg = T // G, C // G
+    slot = np.full((T, k), -1, np.int32)
+    count = np.zeros(E, np.int32)
+    demand = np.zeros(E, np.int32)
+    slot_src = np.full((E, C), -1, np.int32)
+    for g in range(G):
+        a, b = g * Tg, (g + 1) * Tg
+        keys_g = None if rts_keys is None else np.asarray(rts_keys)[a:b]
+        s_g, c_g, d_g, src_g = route(expert_idx[a:b], keys_g, E, Cg)
+        for e in range(E):
+            n = int(c_g[e])
+            slot_src[e, count[e]:count[e] + n] = src_g[e, :n] + a * k    # group-local t*k+j -> global
+        kept = s_g >= 0
+        slot[a:b][kept] = (s_g + count[expert_idx[a:b]])[kept]
+        count += c_g
+        demand += d_g
+    return slot, count, demand, slot_src
+
+
 # --------------------------------------------------------------------------
 # dispatch / combine                                      (Sec. 3.1, Sec. 4.2)
 # --------------------------------------------------------------------------
@@ -350,20 +384,24 @@ def gate_logits_bwd(x, Wg, dlogits):
 # --------------------------------------------------------------------------
 # the whole layer, forward and backward
 # --------------------------------------------------------------------------
-def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None, aux_coef=0.0):
+def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None, aux_coef=0.0, groups=1):
     """One MoE layer forward and backward in the order gate -> capacity/RTS ->
     dispatch -> experts -> combine, then the reverse.  `logits`, when given,
     replaces the gate projection as the routing input (used to route on the
     fp32 logits another implementation produced); the gate projection's
     backward still uses x and Wg.  aux_coef > 0 adds aux_coef * (balancing loss)
     to the objective: its value is returned and its gradient joins dlogits.
+    groups > 1 selects tokens inside groups of T/groups consecutive tokens.
     Returns a dict of every intermediate."""
     E = W1.shape[0]
     lg = gate_logits(x, Wg, bias) if logits is None else np.asarray(logits, _F)
     p = softmax(lg)
     eidx = top_k(lg, k)
     g = gate_weights(p, eidx)
-    slot, count, demand, slot_src = route(eidx, rts_keys, E, C)
+    if groups == 1:
+        slot, count, demand, slot_src = route(eidx, rts_keys, E, C)
+    else:
+        slot, count, demand, slot_src = route_grouped(eidx, rts_keys, E, C, groups)
     Xd = dispatch(x, slot_src, k)
     Z, H, Yd = expert_ffn_fwd(Xd, count, W1, W2, kind)
     y = combine_fwd(Yd, eidx, slot, g)

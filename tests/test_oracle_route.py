@@ -200,3 +200,77 @@ def test_utilisation_counts_every_routed_candidate_and_sums_the_demands():
     assert np.array_equal(u, np.sum(demands, axis=0))
     assert np.array_equal(u, np.bincount(np.concatenate([b.ravel() for b in batches]), minlength=E))
     assert np.array_equal(O.utilisation([], E), np.zeros(E, np.int64))
+
+
+# ---------------------------------------------------------------------------
+# grouped token selection (Sec. 3.1 group dimension, Sec. 5.5 ablation arm)
+# ---------------------------------------------------------------------------
+def brute_grouped(expert_idx, keys, E, C, G):
+    """Independent statement: sort each (group, expert)'s candidates by
+    (choice, -key, token) with Python's sort, keep the first C/G, and lay the
+    groups' kept rows one after another in the expert's buffer."""
+    T, k = expert_idx.shape
+    Tg, Cg = T // G, C // G
+    slot = np.full((T, k), -1, np.int32)
+    slot_src = np.full((E, C), -1, np.int32)
+    count = np.zeros(E, np.int32)
+    for e in range(E):
+        nxt = 0
+        for g in range(G):
+            cands = [(j, -(0.0 if keys is None else float(keys[t])), t)
+                     for t in range(g * Tg, (g + 1) * Tg) for j in range(k) if expert_idx[t, j] == e]
+            for (j, _, t) in sorted(cands)[:Cg]:
+                slot[t, j] = nxt
+                slot_src[e, nxt] = t * k + j
+                nxt += 1
+        count[e] = nxt
+    return slot, count, slot_src
+
+
+@pytest.mark.parametrize("k", [1, 2])
+@pytest.mark.parametrize("use_keys", [True, False])
+def test_grouped_selection_matches_brute_force(k, use_keys):
+    rng = np.random.default_rng(40 + k)
+    T, E, G, C = 96, 5, 4, 24
+    lg = rng.standard_normal((T, E)); lg[:, 0] += 1.0
+    eidx = O.top_k(lg, k)
+    keys = rng.random(T) if use_keys else None
+    if use_keys:
+        keys[10:14] = keys[10]                      # duplicate keys -> token order
+    slot, count, demand, slot_src = O.route_grouped(eidx, keys, E, C, G)
+    bs, bc, bsrc = brute_grouped(eidx, keys, E, C, G)
+    assert np.array_equal(slot, bs) and np.array_equal(count, bc) and np.array_equal(slot_src, bsrc)
+    assert np.array_equal(demand, np.bincount(eidx.ravel(), minlength=E))
+    assert (slot < 0).any()                         # the hot expert overflows its group capacity
+
+
+def test_grouped_with_one_group_is_plain_routing_and_groups_confine_the_position_bias():
+    rng = np.random.default_rng(7)
+    T, E, C = 128, 4, 32
+    eidx = O.top_k(rng.standard_normal((T, E)), 1)
+    a = O.route(eidx, None, E, C)
+    b = O.route_grouped(eidx, None, E, C, 1)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+    # every token wants expert 2, position priority: plain routing keeps the first C
+    # tokens of the batch, grouped routing the first C/G tokens of every group
+    allsame = np.full((T, 1), 2, np.int32)
+    sp = O.route(allsame, None, E, C)[0][:, 0]
+    sg, cg, dg, srcg = O.route_grouped(allsame, None, E, C, 4)
+    assert np.array_equal(np.nonzero(sp >= 0)[0], np.arange(C))
+    kept = np.nonzero(sg[:, 0] >= 0)[0]
+    assert np.array_equal(kept, np.concatenate([np.arange(g * 32, g * 32 + 8) for g in range(4)]))
+    assert np.array_equal(sg[kept, 0], np.arange(C)) and cg[2] == C and dg[2] == T
+    assert np.array_equal(srcg[2], kept)            # k = 1: t*k+j = t
+    # per group and expert never more than C/G rows
+    eidx2 = O.top_k(rng.standard_normal((T, E)), 2)
+    s2, c2, _, src2 = O.route_grouped(eidx2, rng.random(T), E, C, 4)
+    for g in range(4):
+        for e in range(E):
+            assert ((s2[g * 32:(g + 1) * 32] >= 0) & (eidx2[g * 32:(g + 1) * 32] == e)).sum() <= C // 4
+    # slot_src is the inverse of slot on the rows in use, which form a prefix
+    for e in range(E):
+        assert np.all(src2[e, :c2[e]] >= 0) and np.all(src2[e, c2[e]:] == -1)
+        for s in range(c2[e]):
+            t, j = divmod(int(src2[e, s]), 2)
+            assert eidx2[t, j] == e and s2[t, j] == s
