@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--aux-coef", type=float, default=0.0,
                     help="weight of the balancing auxiliary loss (Sec. 5.1 uses 0.01); 0 = the plain hot path")
+    ap.add_argument("--groups", type=int, default=1,
+                    help="grouped token selection inside groups of T/groups consecutive tokens (Sec. 3.1); 1 = plain")
     ap.add_argument("--forward-only", action="store_true",
                     help="evaluation path: forward only, capacity factor 2.0, utilisation counting (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -92,14 +94,16 @@ def main():
 
     x, dy, W1, W2 = dev(d["x"], adt), dev(d["dy"], adt), dev(d["W1"], adt), dev(d["W2"], adt)
     Wg, bias, keys = dev(d["Wg"]), dev(d["bias"]), dev(d["rts_keys"])
-    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act, forward_only=args.forward_only)
+    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act, forward_only=args.forward_only,
+                     groups=args.groups)
     s = layer.shape
     L = layer
 
     calls = [
         ("gate_logits", lambda: B.moe_gate_logits(s, x, Wg, bias, L.logits)),
-        ("gate_route", lambda: B.moe_gate_route(s, L.logits, keys, L.probs, L.expert_idx, L.gate_w, L.slot,
-                                                L.expert_count, L.expert_demand, L.slot_src, L.ws)),
+        ("gate_route", lambda: B.moe_gate_route_grouped(s, args.groups, L.logits, keys, L.probs, L.expert_idx,
+                                                        L.gate_w, L.slot, L.expert_count, L.expert_demand,
+                                                        L.slot_src, L.ws)),
         ("dispatch", lambda: B.moe_dispatch(s, x, L.slot_src, L.expert_count, L.xd)),
         ("expert_ffn_fwd", lambda: B.moe_expert_ffn_fwd(s, L.xd, L.expert_count, W1, W2, L.h, L.dact, L.yd)),
         ("combine_fwd", lambda: B.moe_combine_fwd(s, L.yd, L.expert_idx, L.slot, L.gate_w, L.y)),
@@ -222,7 +226,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k,
                    "capacity": w.capacity, "capacity_factor": w.capacity_factor,
-                   "act": "gelu" if w.act == I.GELU else "relu", "aux_coef": args.aux_coef,
+                   "act": "gelu" if w.act == I.GELU else "relu", "aux_coef": args.aux_coef, "groups": args.groups,
                    "mode": "forward-only (evaluation)" if args.forward_only else "forward+backward (training)",
                    "kept_assignments": M,
                    "expert_demand_max": int(L.expert_demand.max().item()),

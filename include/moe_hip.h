@@ -109,6 +109,23 @@ int moe_gate_route(const moe_shape* shape, const float* logits, const float* rts
                    int32_t* expert_count, int32_t* expert_demand, int32_t* slot_src,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* Grouped token selection (Sec. 3.1: a group dimension batches consecutive
+ * sentences and the selection happens inside each group; the second arm of the
+ * ablation in Sec. 5.5).  As moe_gate_route, except that the T tokens form
+ * n_groups groups of T/n_groups consecutive tokens and every group routes on
+ * its own with capacity/n_groups slots per expert.  The rows an expert keeps
+ * from group 0 come first in its buffer, then those of group 1, ... without
+ * gaps: slot = (rows kept for the expert by earlier groups) + rank inside the
+ * group, so expert_count[e] rows are in use as for plain routing.
+ * Limits for n_groups > 1: T % n_groups == 0, (T/n_groups) % 256 == 0,
+ * capacity % n_groups == 0 (else MOE_ERR_SHAPE).  n_groups == 1 is
+ * moe_gate_route.  Needs workspace. */
+int moe_gate_route_grouped(const moe_shape* shape, int32_t n_groups, const float* logits,
+                           const float* rts_keys_or_null, float* probs, int32_t* expert_idx,
+                           float* gate_w, int32_t* slot, int32_t* expert_count,
+                           int32_t* expert_demand, int32_t* slot_src, void* ws, size_t ws_bytes,
+                           void* stream);
+
 /* Dispatch (Sec. 3.1: fixed-shape per-expert buffers):
  *   xd[e,s,:] = x[slot_src[e,s] / k, :]  for s < expert_count[e]  (bit copies).
  * Its backward is moe_combine_fwd with gate_w_or_null == NULL. */

@@ -18,7 +18,7 @@ EXPORTS = [
     "moe_status_string", "moe_capacity", "moe_workspace_bytes", "moe_gate_logits", "moe_gate_route",
     "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine_fwd", "moe_combine_bwd", "moe_expert_ffn_bwd",
     "moe_gate_bwd", "moe_gate_logits_bwd", "moe_aux_loss", "moe_gate_bwd_aux",
-    "moe_utilisation_accumulate",
+    "moe_utilisation_accumulate", "moe_gate_route_grouped",
 ]
 
 
@@ -65,6 +65,7 @@ def lib():
             "moe_aux_loss": [shp] + [vp] * 6 + [sz, vp],
             "moe_gate_bwd_aux": [shp] + [vp] * 5 + [ctypes.c_float, vp, vp],
             "moe_utilisation_accumulate": [shp, vp, vp, vp],
+            "moe_gate_route_grouped": [shp, i32] + [vp] * 10 + [sz, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -118,6 +119,15 @@ def moe_gate_route(shape, logits, rts_keys, probs, expert_idx, gate_w, slot, exp
                                 _p(expert_demand), _p(slot_src), _p(ws),
                                 0 if ws is None else ws.numel() * ws.element_size(),
                                 _stream(stream)), "moe_gate_route")
+
+
+def moe_gate_route_grouped(shape, n_groups, logits, rts_keys, probs, expert_idx, gate_w, slot, expert_count,
+                           expert_demand, slot_src, ws, stream=None):
+    _check(lib().moe_gate_route_grouped(ctypes.byref(shape), int(n_groups), _p(logits), _p(rts_keys), _p(probs),
+                                        _p(expert_idx), _p(gate_w), _p(slot), _p(expert_count),
+                                        _p(expert_demand), _p(slot_src), _p(ws),
+                                        0 if ws is None else ws.numel() * ws.element_size(),
+                                        _stream(stream)), "moe_gate_route_grouped")
 
 
 def moe_dispatch(shape, x, slot_src, expert_count, xd, stream=None):

@@ -13,6 +13,9 @@
 //   3. route_rank    rank inside a segment by counting the candidates that
 //                    precede it in (key descending, token ascending) order,
 //                    LDS-tiled; slot = rank (+ first-choice demand for j = 1).
+// Grouped token selection (Sec. 3.1) runs the same three kernels with one set
+// of segments per group of consecutive tokens and Cg = C / G slots per group
+// and expert; an expert's kept rows of successive groups are laid end to end.
 // Work is O(T*E + sum over segments of n^2), bounded by the single-expert worst
 // case; balanced routing makes step 3 a few microseconds.
 #include "moe_common.h"
@@ -22,27 +25,30 @@
 
 struct RouteWs {
     int32_t* hist;        // [nchunk][k*E] candidates per chunk and segment
-    int32_t* seg_start;   // [k*E+1] segment seg = e*k+j starts here in seg_tok/seg_key
-    int32_t* tile_start;  // [k*E+1] prefix of ceil(n_seg / RANK_TILE)
+    int32_t* seg_start;   // [G][k*E+1] segment seg = e*k+j of group g starts here in seg_tok/seg_key
+    int32_t* tile_start;  // [G][k*E+1] prefix, inside group g, of ceil(n_seg / RANK_TILE)
+    int32_t* goff;        // [G][E] rows kept for expert e in the groups before g
     int32_t* seg_tok;     // [T*k]
     float* seg_key;       // [T*k]
 };
 
 static inline int n_chunks(const moe_shape* s) { return ceil_div(s->T, CHUNK); }
 
+// Sized for the largest possible number of groups (one per chunk).
 size_t route_ws_bytes(const moe_shape* s) {
-    const size_t kE = (size_t)s->k * s->E, Tk = (size_t)s->T * s->k;
-    return align_up((size_t)n_chunks(s) * kE * 4, 256) + 2 * align_up((kE + 1) * 4, 256) +
+    const size_t kE = (size_t)s->k * s->E, Tk = (size_t)s->T * s->k, G = (size_t)n_chunks(s);
+    return align_up(G * kE * 4, 256) + 2 * align_up(G * (kE + 1) * 4, 256) + align_up(G * s->E * 4, 256) +
            2 * align_up(Tk * 4, 256);
 }
 
 static RouteWs carve(const moe_shape* s, void* ws) {
-    const size_t kE = (size_t)s->k * s->E, Tk = (size_t)s->T * s->k;
+    const size_t kE = (size_t)s->k * s->E, Tk = (size_t)s->T * s->k, G = (size_t)n_chunks(s);
     char* p = (char*)ws;
     RouteWs r;
-    r.hist = (int32_t*)p;       p += align_up((size_t)n_chunks(s) * kE * 4, 256);
-    r.seg_start = (int32_t*)p;  p += align_up((kE + 1) * 4, 256);
-    r.tile_start = (int32_t*)p; p += align_up((kE + 1) * 4, 256);
+    r.hist = (int32_t*)p;       p += align_up(G * kE * 4, 256);
+    r.seg_start = (int32_t*)p;  p += align_up(G * (kE + 1) * 4, 256);
+    r.tile_start = (int32_t*)p; p += align_up(G * (kE + 1) * 4, 256);
+    r.goff = (int32_t*)p;       p += align_up(G * s->E * 4, 256);
     r.seg_tok = (int32_t*)p;    p += align_up(Tk * 4, 256);
     r.seg_key = (float*)p;
     return r;
@@ -165,22 +171,27 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
     return v;
 }
 
+// Groups (grouped token selection, Sec. 3.1): chunks [g*cpg, (g+1)*cpg) form group
+// g, which routes on its own with Cg slots per expert; its candidates occupy
+// positions [g*cpg*CHUNK*k, ...) of seg_tok/seg_key.  One group = plain routing.
 __global__ __launch_bounds__(CHUNK) void route_place_kernel(
-    int T, int E, int k, int C, int nchunk, const int32_t* __restrict__ expert_idx,
+    int T, int E, int k, int Cg, int nchunk, int cpg, const int32_t* __restrict__ expert_idx,
     const float* __restrict__ keys, const int32_t* __restrict__ hist,
-    int32_t* __restrict__ seg_start, int32_t* __restrict__ tile_start,
+    int32_t* __restrict__ seg_start, int32_t* __restrict__ tile_start, int32_t* __restrict__ goff,
     int32_t* __restrict__ expert_count, int32_t* __restrict__ expert_demand,
     int32_t* __restrict__ seg_tok, float* __restrict__ seg_key) {
-    __shared__ int32_t s_tot[512];          // candidates per segment, whole batch
-    __shared__ int32_t s_base[512];         // segment start + candidates in earlier chunks
+    __shared__ int32_t s_tot[512];          // candidates per segment, whole group
+    __shared__ int32_t s_base[512];         // segment start + candidates in the group's earlier chunks
     __shared__ int32_t s_wcnt[CHUNK / 64][512];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int chunk = blockIdx.x;
     const int kE = k * E;
+    const int g = chunk / cpg, c_lo = g * cpg, c_hi = min(c_lo + cpg, nchunk);
+    const bool leader = chunk == c_lo;      // publishes the group's tables
     for (int seg = threadIdx.x; seg < kE; seg += CHUNK) {
         int tot = 0, pre = 0;
-        int c = 0;
-        for (; c + 8 <= nchunk; c += 8) {   // 8 independent loads in flight
+        int c = c_lo;
+        for (; c + 8 <= c_hi; c += 8) {   // 8 independent loads in flight
             int v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) v[u] = hist[(size_t)(c + u) * kE + seg];
@@ -190,7 +201,7 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
                 tot += v[u];
             }
         }
-        for (; c < nchunk; ++c) {
+        for (; c < c_hi; ++c) {
             const int v = hist[(size_t)c * kE + seg];
             pre += c < chunk ? v : 0;
             tot += v;
@@ -201,8 +212,45 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
         for (int w = 0; w < CHUNK / 64; ++w) s_wcnt[w][seg] = 0;
     }
     __syncthreads();
-    if (wave == 0) {  // exclusive scan over segments (seg = e*k+j)
-        int run_pos = 0, run_tile = 0;
+    if (leader && threadIdx.x < E) {
+        // rows kept for this expert by the groups before g (chunk 0: also the totals)
+        const int e = threadIdx.x;
+        const int ngroups = (nchunk + cpg - 1) / cpg;
+        const int upto = chunk == 0 ? ngroups : g;
+        int off = 0, dem_tot = 0, cnt_tot = 0;
+        for (int gg = 0; gg < upto; ++gg) {
+            int dem = 0;
+            const int hi = min((gg + 1) * cpg, nchunk);
+            int c = gg * cpg;
+            for (; c + 8 <= hi; c += 8) {
+                int v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    v[u] = hist[(size_t)(c + u) * kE + e * k];
+                    if (k == 2) v[u] += hist[(size_t)(c + u) * kE + e * k + 1];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) dem += v[u];
+            }
+            for (; c < hi; ++c) {
+                dem += hist[(size_t)c * kE + e * k];
+                if (k == 2) dem += hist[(size_t)c * kE + e * k + 1];
+            }
+            const int kept = dem < Cg ? dem : Cg;
+            if (gg < g) off += kept;
+            dem_tot += dem;
+            cnt_tot += kept;
+        }
+        goff[(size_t)g * E + e] = off;
+        if (chunk == 0) {
+            expert_demand[e] = dem_tot;
+            expert_count[e] = cnt_tot;
+        }
+    }
+    if (wave == 0) {  // exclusive scan over the group's segments (seg = e*k+j)
+        int run_pos = c_lo * CHUNK * k, run_tile = 0;   // every token before the group has k candidates
+        int32_t* gs = seg_start + (size_t)g * (kE + 1);
+        int32_t* gt = tile_start + (size_t)g * (kE + 1);
         for (int s0 = 0; s0 < kE; s0 += 64) {
             const int seg = s0 + lane;
             const int n = seg < kE ? s_tot[seg] : 0;
@@ -211,25 +259,17 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
             if (seg < kE) {
                 const int start = run_pos + ip - n;
                 s_base[seg] += start;
-                if (chunk == 0) {
-                    seg_start[seg] = start;
-                    tile_start[seg] = run_tile + it - nt;
+                if (leader) {
+                    gs[seg] = start;
+                    gt[seg] = run_tile + it - nt;
                 }
             }
             run_pos += __shfl(ip, 63, MOE_WAVE);
             run_tile += __shfl(it, 63, MOE_WAVE);
         }
-        if (chunk == 0) {
-            if (lane == 0) {
-                seg_start[kE] = run_pos;
-                tile_start[kE] = run_tile;
-            }
-            for (int e = lane; e < E; e += 64) {
-                int dem = s_tot[e * k];
-                if (k == 2) dem += s_tot[e * k + 1];
-                expert_demand[e] = dem;
-                expert_count[e] = dem < C ? dem : C;
-            }
+        if (leader && lane == 0) {
+            gs[kE] = run_pos;
+            gt[kE] = run_tile;
         }
     }
     __syncthreads();
@@ -266,14 +306,18 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
 // 3. rank inside the segment, slots, slot_src
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(RANK_TILE) void route_rank_kernel(
-    int E, int k, int C, int has_keys, const int32_t* __restrict__ seg_start,
-    const int32_t* __restrict__ tile_start, const int32_t* __restrict__ seg_tok,
+    int E, int k, int C, int Cg, int tiles_per_group, int has_keys, const int32_t* __restrict__ seg_start_all,
+    const int32_t* __restrict__ tile_start_all, const int32_t* __restrict__ goff,
+    const int32_t* __restrict__ expert_count, const int32_t* __restrict__ seg_tok,
     const float* __restrict__ seg_key, int32_t* __restrict__ slot, int32_t* __restrict__ slot_src) {
     __shared__ float s_key[RANK_TILE];
     __shared__ int s_seg;
     const int kE = k * E;
     const int tid = threadIdx.x;
-    const int b = blockIdx.x;
+    const int grp = blockIdx.x / tiles_per_group;
+    const int b = blockIdx.x - grp * tiles_per_group;       // tile inside the group
+    const int32_t* seg_start = seg_start_all + (size_t)grp * (kE + 1);
+    const int32_t* tile_start = tile_start_all + (size_t)grp * (kE + 1);
     // segment owning tile b: the one with tile_start[seg] <= b < tile_start[seg+1]
     // (empty segments have an empty range); found by all threads in parallel
     if (tid == 0) s_seg = -1;
@@ -311,19 +355,53 @@ __global__ __launch_bounds__(RANK_TILE) void route_rank_kernel(
         if (valid) {
             const int e = seg / k, j = seg - e * k;
             const int base = j == 1 ? s0 - seg_start[seg - 1] : 0;  // first choices go first
-            const int rank = base + cnt;
+            const int rank = base + cnt;                            // inside (group, expert)
             const int cand = seg_tok[p] * k + j;
-            slot[cand] = rank < C ? rank : -1;
-            if (rank < C) slot_src[(size_t)e * C + rank] = cand;
+            const int row = goff[(size_t)grp * E + e] + rank;       // earlier groups' rows come first
+            slot[cand] = rank < Cg ? row : -1;
+            if (rank < Cg) slot_src[(size_t)e * C + row] = cand;
         }
     }
     // unused slots
     const int total = E * C;
-    for (int idx = b * RANK_TILE + tid; idx < total; idx += gridDim.x * RANK_TILE) {
-        const int e = idx / C, s = idx - e * C;
-        const int dem = seg_start[(e + 1) * k] - seg_start[e * k];
-        if (s >= dem) slot_src[idx] = -1;
+    for (int idx = blockIdx.x * RANK_TILE + tid; idx < total; idx += gridDim.x * RANK_TILE) {
+        const int e = idx / C, sl = idx - e * C;
+        if (sl >= expert_count[e]) slot_src[idx] = -1;
     }
+}
+
+static int route_impl(const moe_shape* shape, int G, const float* logits, const float* rts_keys_or_null,
+                      float* probs, int32_t* expert_idx, float* gate_w, int32_t* slot,
+                      int32_t* expert_count, int32_t* expert_demand, int32_t* slot_src, void* ws,
+                      size_t ws_bytes, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!logits || !probs || !expert_idx || !gate_w || !slot || !expert_count || !expert_demand ||
+        !slot_src)
+        return MOE_ERR_NULL;
+    const int T = shape->T, E = shape->E, k = shape->k, C = shape->capacity;
+    if (G < 1) return MOE_ERR_SHAPE;
+    if (G > 1 && (T % G || (T / G) % CHUNK || C % G)) return MOE_ERR_SHAPE;
+    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < route_ws_bytes(shape)) return MOE_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const RouteWs r = carve(shape, ws);
+    const int nchunk = n_chunks(shape);
+    const int cpg = G == 1 ? nchunk : T / G / CHUNK;    // chunks per group
+    const int Cg = C / G;
+#define GATE(LPT) gate_topk_kernel<LPT><<<nchunk, CHUNK, 0, st>>>(T, E, k, logits, probs, expert_idx, gate_w, r.hist)
+    if (E <= 4) GATE(1); else if (E <= 8) GATE(2); else if (E <= 16) GATE(4); else if (E <= 32) GATE(8);
+    else if (E <= 64) GATE(16); else if (E <= 128) GATE(32); else GATE(64);
+#undef GATE
+    route_place_kernel<<<nchunk, CHUNK, 0, st>>>(T, E, k, Cg, nchunk, cpg, expert_idx, rts_keys_or_null, r.hist,
+                                                 r.seg_start, r.tile_start, r.goff, expert_count,
+                                                 expert_demand, r.seg_tok, r.seg_key);
+    const int Tg = G == 1 ? T : T / G;
+    const int tiles_per_group = ceil_div(Tg * k, RANK_TILE) + k * E;
+    route_rank_kernel<<<G * tiles_per_group, RANK_TILE, 0, st>>>(E, k, C, Cg, tiles_per_group,
+                                                                 rts_keys_or_null != nullptr, r.seg_start,
+                                                                 r.tile_start, r.goff, expert_count, r.seg_tok,
+                                                                 r.seg_key, slot, slot_src);
+    return launch_status();
 }
 
 extern "C" int moe_gate_route(const moe_shape* shape, const float* logits,
@@ -331,26 +409,15 @@ extern "C" int moe_gate_route(const moe_shape* shape, const float* logits,
                               float* gate_w, int32_t* slot, int32_t* expert_count,
                               int32_t* expert_demand, int32_t* slot_src, void* ws, size_t ws_bytes,
                               void* stream) {
-    int rc = check_shape(shape);
-    if (rc) return rc;
-    if (!logits || !probs || !expert_idx || !gate_w || !slot || !expert_count || !expert_demand ||
-        !slot_src)
-        return MOE_ERR_NULL;
-    if (!ws || ((uintptr_t)ws & 255) || ws_bytes < route_ws_bytes(shape)) return MOE_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-    const int T = shape->T, E = shape->E, k = shape->k, C = shape->capacity;
-    const RouteWs r = carve(shape, ws);
-    const int nchunk = n_chunks(shape);
-#define GATE(LPT) gate_topk_kernel<LPT><<<nchunk, CHUNK, 0, st>>>(T, E, k, logits, probs, expert_idx, gate_w, r.hist)
-    if (E <= 4) GATE(1); else if (E <= 8) GATE(2); else if (E <= 16) GATE(4); else if (E <= 32) GATE(8);
-    else if (E <= 64) GATE(16); else if (E <= 128) GATE(32); else GATE(64);
-#undef GATE
-    route_place_kernel<<<nchunk, CHUNK, 0, st>>>(T, E, k, C, nchunk, expert_idx, rts_keys_or_null, r.hist,
-                                                 r.seg_start, r.tile_start, expert_count, expert_demand,
-                                                 r.seg_tok, r.seg_key);
-    const int ntile_max = ceil_div(T * k, RANK_TILE) + k * E;
-    route_rank_kernel<<<ntile_max, RANK_TILE, 0, st>>>(E, k, C, rts_keys_or_null != nullptr,
-                                                       r.seg_start, r.tile_start, r.seg_tok,
-                                                       r.seg_key, slot, slot_src);
-    return launch_status();
+    return route_impl(shape, 1, logits, rts_keys_or_null, probs, expert_idx, gate_w, slot, expert_count,
+                      expert_demand, slot_src, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_gate_route_grouped(const moe_shape* shape, int32_t n_groups, const float* logits,
+                                      const float* rts_keys_or_null, float* probs, int32_t* expert_idx,
+                                      float* gate_w, int32_t* slot, int32_t* expert_count,
+                                      int32_t* expert_demand, int32_t* slot_src, void* ws,
+                                      size_t ws_bytes, void* stream) {
+    return route_impl(shape, n_groups, logits, rts_keys_or_null, probs, expert_idx, gate_w, slot, expert_count,
+                      expert_demand, slot_src, ws, ws_bytes, stream);
 }

@@ -13,7 +13,7 @@ _TORCH_DT = {B.F32: torch.float32, B.BF16: torch.bfloat16}
 
 class MoELayer:
     def __init__(self, T, d_model, d_ff, E, k, capacity, dtype, act, device="cuda:0", aux_coef=0.0,
-                 forward_only=False):
+                 forward_only=False, groups=1):
         if not torch.cuda.is_available():
             raise B.MoeError("MoELayer needs a GPU; there is no CPU fallback")
         B.lib()
@@ -21,6 +21,7 @@ class MoELayer:
         self.T, self.d, self.f, self.E, self.k, self.C = T, d_model, d_ff, E, k, capacity
         self.device = torch.device(device)
         self.aux_coef = float(aux_coef)     # weight of the balancing loss in the objective (0 = off)
+        self.groups = int(groups)           # > 1: token selection inside groups of T/groups consecutive tokens
         self.forward_only = bool(forward_only)   # evaluation: no saved derivative, no backward buffers
         adt = _TORCH_DT[dtype]
         dev = self.device
@@ -71,8 +72,13 @@ class MoELayer:
             B.moe_gate_logits(s, x, Wg, bias, self.logits)
         else:
             self.logits.copy_(logits)
-        B.moe_gate_route(s, self.logits, rts_keys, self.probs, self.expert_idx, self.gate_w,
-                         self.slot, self.expert_count, self.expert_demand, self.slot_src, self.ws)
+        if self.groups > 1:
+            B.moe_gate_route_grouped(s, self.groups, self.logits, rts_keys, self.probs, self.expert_idx,
+                                     self.gate_w, self.slot, self.expert_count, self.expert_demand,
+                                     self.slot_src, self.ws)
+        else:
+            B.moe_gate_route(s, self.logits, rts_keys, self.probs, self.expert_idx, self.gate_w,
+                             self.slot, self.expert_count, self.expert_demand, self.slot_src, self.ws)
         if self.forward_only:
             B.moe_utilisation_accumulate(s, self.expert_demand, self.utilisation)
         if self.aux_coef != 0.0:

@@ -32,11 +32,11 @@ def rel_l2(got, want):
     return num / den if den > 0 else num
 
 
-def run_layer(w, d, use_keys=True, logits=None, aux_coef=0.0):
+def run_layer(w, d, use_keys=True, logits=None, aux_coef=0.0, groups=1):
     """One forward+backward of workload w on the GPU; returns (layer, dict of
     host arrays) with the same names the oracle uses.  logits (fp32 numpy, made
     by the oracle) replaces the GPU's gate projection as the router's input."""
-    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act, aux_coef=aux_coef)
+    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act, aux_coef=aux_coef, groups=groups)
     x, dy = to_dev(d["x"], w.dtype), to_dev(d["dy"], w.dtype)
     W1, W2 = to_dev(d["W1"], w.dtype), to_dev(d["W2"], w.dtype)
     Wg = to_dev(d["Wg"], I.F32)
