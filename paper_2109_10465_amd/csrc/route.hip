@@ -218,7 +218,11 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
         const int ngroups = (nchunk + cpg - 1) / cpg;
         const int upto = chunk == 0 ? ngroups : g;
         int off = 0, dem_tot = 0, cnt_tot = 0;
-        for (int gg = 0; gg < upto; ++gg) {
+        if (ngroups == 1) {      // plain routing: the group totals are the batch totals
+            dem_tot = s_tot[e * k] + (k == 2 ? s_tot[e * k + 1] : 0);
+            cnt_tot = dem_tot < Cg ? dem_tot : Cg;
+        }
+        for (int gg = 0; gg < (ngroups == 1 ? 0 : upto); ++gg) {
             int dem = 0;
             const int hi = min((gg + 1) * cpg, nchunk);
             int c = gg * cpg;
