@@ -4,91 +4,95 @@
 #include "moe_common.h"
 
 // ---------------------------------------------------------------------------
-// logits[T,E] = x[T,d] * Wg[d,E] (+ bias)
-// Workgroup: 64 tokens; experts in passes of 32.  Thread (ty,tx) owns a 2-token
-// x 4-expert register tile, so one 8-byte and one 16-byte LDS read feed 8 FMAs.
-// x is staged transposed ([k][token]) and Wg as is ([k][expert]) in slabs of
-// GL_DK reduction entries; every output is one sequential fp32 FMA chain.
+// logits[T,E] = x[T,d] * Wg[d,E] (+ bias)   on the fp32 matrix pipe
+// Workgroup: 32 tokens x all experts, 8 waves that split the reduction over d.
+// v_mfma_f32_32x32x2_f32: lane (r = l%32, h = l/32) supplies A[token r][k] and
+// B[k][expert r] for ONE k per instruction.  The order of a reduction is free,
+// so a lane's 8 consecutive x values (one 16-byte load for bf16) serve 8
+// instructions: in a 16-deep block, instruction s uses k = 8h + s.  Wg (L2
+// resident) is read as 128-byte rows.  All loads of a group of blocks are in
+// flight before the first MFMA; other waves cover the latency.  The 8 partial
+// tiles are added in wave order through LDS, so the result is reproducible.
 // ---------------------------------------------------------------------------
-#define GL_TB 64
-#define GL_DK 64
+#define GLM_KSPLIT 8
+typedef float glm_f32x16 __attribute__((ext_vector_type(16)));
 
 template <typename T>
-__global__ __launch_bounds__(256) void gate_logits_kernel(
+__device__ __forceinline__ void load8(__amdgpu_buffer_rsrc_t rs, uint32_t off, float (&v)[8]);
+template <>
+__device__ __forceinline__ void load8<bf16_t>(__amdgpu_buffer_rsrc_t rs, uint32_t off, float (&v)[8]) {
+    BufChunk<bf16_t>::load(rs, off, v);
+}
+template <>
+__device__ __forceinline__ void load8<float>(__amdgpu_buffer_rsrc_t rs, uint32_t off, float (&v)[8]) {
+    float lo[4], hi[4];
+    BufChunk<float>::load(rs, off, lo);
+    BufChunk<float>::load(rs, off == BUF_OOB ? BUF_OOB : off + 16, hi);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = lo[i]; v[4 + i] = hi[i]; }
+}
+
+template <typename T, int NB>
+__global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
     int Tn, int d, int E, const T* __restrict__ x, const float* __restrict__ Wg,
     const float* __restrict__ bias, float* __restrict__ logits) {
-    __shared__ float xs[GL_DK][GL_TB + 4];
-    __shared__ __align__(16) float ws[GL_DK][32];
-    const int tid = threadIdx.x, ty = tid >> 3, tx = tid & 7;
-    const int t0 = blockIdx.x * GL_TB;
-    constexpr int CN = Chunk<T>::N;
-    constexpr int CPR = GL_DK / CN;  // 16-byte chunks per token row of the slab
-    const int rows_here = min(GL_TB, Tn - t0);
+    constexpr int GRP = NB <= 2 ? 8 : 4;   // 16-deep blocks whose loads are in flight together
+    __shared__ float red[GLM_KSPLIT][32][33];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int t0 = blockIdx.x * 32;
+    const int rows_here = min(32, Tn - t0);
     const __amdgpu_buffer_rsrc_t rs_x = buf_rsrc(x + (size_t)t0 * d, (size_t)rows_here * d * sizeof(T));
     const __amdgpu_buffer_rsrc_t rs_w = buf_rsrc(Wg, (size_t)d * E * 4);
-    constexpr int XPT = GL_TB * CPR / 256;   // x chunks per thread per slab
-    constexpr int WPT = GL_DK * 32 / 256;    // Wg entries per thread per slab
-    static_assert(GL_TB * CPR % 256 == 0, "slab must divide over the workgroup");
-    for (int e0 = 0; e0 < E; e0 += 32) {
-        float acc[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-        float xr[XPT][CN], wr[WPT];
-        // slab k0 -> registers (zero outside the tensors)
-        auto fetch = [&](int k0) {   // branch free: out-of-range lanes read zeros
+    const int nblk = (d + 15) / 16;
+    const int per_wave = (nblk + GLM_KSPLIT - 1) / GLM_KSPLIT;
+    const int b_lo = wave * per_wave, b_hi = min(nblk, b_lo + per_wave);
+    glm_f32x16 acc[NB];
 #pragma unroll
-            for (int j = 0; j < XPT; ++j) {
-                const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
-                const bool ok = k0 + cc * CN < d;    // rows beyond T fall outside rs_x
-                BufChunk<T>::load(rs_x, ok ? (uint32_t)((r * d + k0 + cc * CN) * sizeof(T)) : BUF_OOB, xr[j]);
-            }
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int j = 0; j < WPT; ++j) {
-                const int c = tid + j * 256, r = c >> 5, e = c & 31;
-                const bool ok = e0 + e < E;          // rows beyond d fall outside rs_w
-                wr[j] = buf_load_f32(rs_w, ok ? (uint32_t)(((k0 + r) * E + e0 + e) * 4) : BUF_OOB);
-            }
-        };
-        fetch(0);
-        for (int k0 = 0; k0 < d; k0 += GL_DK) {
-            __syncthreads();
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+    for (int b0 = b_lo; b0 < b_hi; b0 += GRP) {
+        float a[GRP][8];
 #pragma unroll
-            for (int j = 0; j < XPT; ++j) {
-                const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
-#pragma unroll
-                for (int i = 0; i < CN; ++i) xs[cc * CN + i][r] = xr[j][i];
-            }
-#pragma unroll
-            for (int j = 0; j < WPT; ++j) {
-                const int c = tid + j * 256;
-                ws[c >> 5][c & 31] = wr[j];
-            }
-            __syncthreads();
-            if (k0 + GL_DK < d) fetch(k0 + GL_DK);   // next slab travels while this one is used
-            for (int kb = 0; kb < GL_DK; kb += 8) {   // 16 LDS reads in flight, then 64 FMAs
-                float2 xv[8];
-                float4 wv[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    xv[u] = *reinterpret_cast<const float2*>(&xs[kb + u][ty * 2]);
-                    wv[u] = *reinterpret_cast<const float4*>(&ws[kb + u][tx * 4]);
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    acc[0][0] = fmaf(xv[u].x, wv[u].x, acc[0][0]); acc[0][1] = fmaf(xv[u].x, wv[u].y, acc[0][1]);
-                    acc[0][2] = fmaf(xv[u].x, wv[u].z, acc[0][2]); acc[0][3] = fmaf(xv[u].x, wv[u].w, acc[0][3]);
-                    acc[1][0] = fmaf(xv[u].y, wv[u].x, acc[1][0]); acc[1][1] = fmaf(xv[u].y, wv[u].y, acc[1][1]);
-                    acc[1][2] = fmaf(xv[u].y, wv[u].z, acc[1][2]); acc[1][3] = fmaf(xv[u].y, wv[u].w, acc[1][3]);
-                }
-            }
+        for (int u = 0; u < GRP; ++u) {
+            const int k = (b0 + u) * 16 + 8 * h;
+            const bool ok = b0 + u < b_hi && k < d;     // rows beyond T fall outside rs_x
+            load8<T>(rs_x, ok ? (uint32_t)((r * d + k) * sizeof(T)) : BUF_OOB, a[u]);
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int t = t0 + ty * 2 + i;
-            if (t >= Tn) continue;
+        for (int nb = 0; nb < NB; ++nb) {
+            float bw[GRP][8];
+            const bool col_ok = nb * 32 + r < E;
 #pragma unroll
-            for (int a = 0; a < 4; ++a) {
-                const int e = e0 + tx * 4 + a;
-                if (e < E) logits[(size_t)t * E + e] = acc[i][a] + (bias ? bias[e] : 0.0f);
-            }
+            for (int u = 0; u < GRP; ++u)
+#pragma unroll
+                for (int s_ = 0; s_ < 8; ++s_) {
+                    const int k = (b0 + u) * 16 + 8 * h + s_;   // rows beyond d fall outside rs_w
+                    const bool ok = col_ok && b0 + u < b_hi;
+                    bw[u][s_] = buf_load_f32(rs_w, ok ? (uint32_t)((k * E + nb * 32 + r) * 4) : BUF_OOB);
+                }
+#pragma unroll
+            for (int u = 0; u < GRP; ++u)
+#pragma unroll
+                for (int s_ = 0; s_ < 8; ++s_)
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][s_], bw[u][s_], acc[nb], 0, 0, 0);
+        }
+    }
+    // accumulator element v of lane l: expert column l%32, token row 8*(v/4) + 4*(l/32) + v%4
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        if (nb) __syncthreads();
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][8 * (v >> 2) + 4 * h + (v & 3)][r] = acc[nb][v];
+        __syncthreads();
+#pragma unroll
+        for (int o = threadIdx.x; o < 32 * 32; o += 64 * GLM_KSPLIT) {
+            const int m = o >> 5, n = o & 31, e = nb * 32 + n;
+            float sum = 0.0f;
+#pragma unroll
+            for (int w = 0; w < GLM_KSPLIT; ++w) sum += red[w][m][n];
+            if (m < rows_here && e < E) logits[(size_t)(t0 + m) * E + e] = sum + (bias ? bias[e] : 0.0f);
         }
     }
 }
@@ -96,8 +100,10 @@ __global__ __launch_bounds__(256) void gate_logits_kernel(
 template <typename T>
 static void launch_gate_logits(const moe_shape* s, const void* x, const float* Wg, const float* bias,
                                float* logits, hipStream_t st) {
-    gate_logits_kernel<T><<<ceil_div(s->T, GL_TB), 256, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg,
-                                                                  bias, logits);
+    const int grid = ceil_div(s->T, 32);
+#define GLM(NB) gate_logits_kernel<T, NB><<<grid, 64 * GLM_KSPLIT, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits)
+    if (s->E <= 32) GLM(1); else if (s->E <= 64) GLM(2); else if (s->E <= 128) GLM(4); else GLM(8);
+#undef GLM
 }
 
 extern "C" int moe_gate_logits(const moe_shape* shape, const void* x, const float* Wg,
