@@ -273,116 +273,82 @@ __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(int n, int nchunk,
 }
 
 // ---------------------------------------------------------------------------
-// dx[t,:] += dlogits[t,:] * Wg^T
-// Workgroup: 64 tokens, loops over 64-column slabs of d; thread (ty,tx) owns a
-// 4-token x 4-column register tile; dlogits and Wg are staged transposed
-// ([expert][token], [expert][column]) so both operands are 16-byte LDS reads.
+// dx[t,:] += dlogits[t,:] * Wg^T   on the fp32 matrix pipe
+// Workgroup: 32 tokens, 8 waves; wave w takes the 32-column blocks w, w+8, ...
+// of d.  The product is formed transposed, D[column][token], so that a lane's
+// accumulators (4 consecutive rows of D at 4 places) are 4 consecutive columns of
+// ONE token row (16 consecutive ones after a permutation of the tile's rows): dx
+// is updated in place with 16-byte accesses and no LDS.
+// A = Wg rows (column i, all experts), B = dlogits rows (token, all experts):
+// both are contiguous along the reduction, so a lane half reads its 16 experts
+// of a 32-expert block as 64 contiguous bytes (instruction s uses expert 16h+s).
 // ---------------------------------------------------------------------------
-#define GX_TB 64
+template <bool VEC>
+__device__ __forceinline__ void load16(__amdgpu_buffer_rsrc_t rs, int row_elems, int e0, int E, float (&v)[16]) {
+    // 16 consecutive fp32 of one row starting at element e0 of the row (row_elems = row * E)
+    if constexpr (VEC) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float q[4];
+            BufChunk<float>::load(rs, e0 + 4 * c < E ? (uint32_t)((row_elems + e0 + 4 * c) * 4) : BUF_OOB, q);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[4 * c + j] = q[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            v[j] = buf_load_f32(rs, e0 + j < E ? (uint32_t)((row_elems + e0 + j) * 4) : BUF_OOB);
+    }
+}
 
-template <typename T>
-__global__ __launch_bounds__(256) void gate_dx_kernel(int Tn, int d, int E,
+template <typename T, int EB, bool VEC>   // EB = 32-expert blocks (E <= 32*EB); VEC: E % 4 == 0
+__global__ __launch_bounds__(512) void gate_dx_kernel(int Tn, int d, int E,
                                                       const float* __restrict__ dlogits,
                                                       const float* __restrict__ Wg,
                                                       T* __restrict__ dx) {
-    extern __shared__ __align__(16) float smem[];
-    float* dls = smem;                     // [E][GX_TB + 4]
-    float* wgs = smem + E * (GX_TB + 4);   // [min(E,64)][64 + 4]
-    constexpr int LD = GX_TB + 4;
-    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
-    const int t0 = blockIdx.x * GX_TB;
-    const int rows_here = min(GX_TB, Tn - t0);
+    constexpr bool HOIST = EB <= 2;      // dlogits fragments stay in registers across column blocks
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int t0 = blockIdx.x * 32;
+    const int rows_here = min(32, Tn - t0);
     const __amdgpu_buffer_rsrc_t rs_dl = buf_rsrc(dlogits + (size_t)t0 * E, (size_t)rows_here * E * 4);
     const __amdgpu_buffer_rsrc_t rs_w = buf_rsrc(Wg, (size_t)d * E * 4);
     const __amdgpu_buffer_rsrc_t rs_dx = buf_rsrc(dx + (size_t)t0 * d, (size_t)rows_here * d * sizeof(T));
-    for (int c0 = 0; c0 < GX_TB * E; c0 += 1024) {   // 4 loads in flight; rows beyond T read zeros
-        float v[4];
+    float bfr[HOIST ? EB : 1][16];
+    if constexpr (HOIST) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = buf_load_f32(rs_dl, (uint32_t)(c0 + u * 256 + tid) * 4);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = c0 + u * 256 + tid, r = c / E, e = c - r * E;
-            if (c < GX_TB * E) dls[e * LD + r] = v[u];
-        }
+        for (int eb = 0; eb < EB; ++eb) load16<VEC>(rs_dl, r * E, eb * 32 + 16 * h, E, bfr[eb]);   // rows beyond T read zeros
     }
-    // E <= 64: the Wg slab of the next 64 columns is prefetched into registers and
-    // the dx values to be updated are requested before the FMA loop, so neither
-    // latency is exposed; E > 64 falls back to slab-by-slab staging.
-    typedef typename Vec4io<T>::raw raw;
-    constexpr int WPT = 64 * 64 / 256;
-    float wr[WPT];
-    // thread -> column rows r = tid/16 + 16*jr, experts e = tid%16 + 16*je of the 64 x 64 slab:
-    // 64 contiguous bytes per row and load, no divisions
-    const int wr_r = tid >> 4, wr_e = tid & 15;
-    auto fetch_w = [&](int i0, int e0, int ne) {
+    const int ncb = (d + 31) / 32;
+    // Row m of the product tile stands for column i0 + pi(m) of the block, with
+    // pi(8q + 4h' + j) = 16h' + 4q + j: a lane's accumulator v (row 8(v/4) + 4h + v%4)
+    // is then column i0 + 16h + v, i.e. 16 CONSECUTIVE columns of its token row.
+    const int a_col = 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);   // pi(r): the Wg row this lane supplies
+    constexpr int CN = BufChunk<T>::N, NCH = 16 / CN;                 // 16-byte pieces of the lane's 16 columns
+    for (int cb = wave; cb < ncb; cb += 8) {
+        const int i0 = cb * 32;
+        const int c0 = i0 + 16 * h;
+        float cur[NCH][CN];
 #pragma unroll
-        for (int jr = 0; jr < 4; ++jr)
+        for (int q = 0; q < NCH; ++q)   // d % 8 == 0: a piece is inside the row or wholly beyond it
+            BufChunk<T>::load(rs_dx, c0 + q * CN < d ? (uint32_t)((r * d + c0 + q * CN) * sizeof(T)) : BUF_OOB, cur[q]);
+        glm_f32x16 acc;
 #pragma unroll
-            for (int je = 0; je < 4; ++je) {
-                const int r = wr_r + 16 * jr, e = wr_e + 16 * je;
-                // rows beyond d fall outside rs_w
-                wr[jr * 4 + je] = buf_load_f32(rs_w, e < ne ? (uint32_t)(((i0 + r) * E + e0 + e) * 4) : BUF_OOB);
-            }
-    };
-    auto commit_w = [&](int ne) {   // experts >= ne are stored as zeros and never read
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll
-        for (int jr = 0; jr < 4; ++jr)
+        for (int eb = 0; eb < EB; ++eb) {
+            float afr[16];
+            load16<VEC>(rs_w, (i0 + a_col) * E, eb * 32 + 16 * h, E, afr);   // rows beyond d fall outside rs_w
+            if constexpr (!HOIST) load16<VEC>(rs_dl, r * E, eb * 32 + 16 * h, E, bfr[0]);
 #pragma unroll
-            for (int je = 0; je < 4; ++je) {
-                const int r = wr_r + 16 * jr, e = wr_e + 16 * je;
-                if (e < min(E, 64)) wgs[e * LD + r] = wr[jr * 4 + je];
-            }
-    };
-    const bool single = E <= 64;
-    if (single) fetch_w(0, 0, E);
-    for (int i0 = 0; i0 < d; i0 += 64) {
-        float acc[4][4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a)
-#pragma unroll
-            for (int b = 0; b < 4; ++b) acc[a][b] = 0.0f;
-        const int i = i0 + tx * 4;
-        raw cur_raw[4];
-#pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            // rows beyond T fall outside rs_dx
-            cur_raw[a] = Vec4buf<T>::load(rs_dx, i < d ? (uint32_t)(((ty * 4 + a) * d + i) * sizeof(T)) : BUF_OOB);
-        }
-        for (int e0 = 0; e0 < E; e0 += 64) {
-            const int ne = min(64, E - e0);
-            if (!single) fetch_w(i0, e0, ne);
-            __syncthreads();
-            commit_w(ne);
-            __syncthreads();
-            if (single && i0 + 64 < d) fetch_w(i0 + 64, 0, E);
-            for (int eb = 0; eb < ne; eb += 4) {   // 8 LDS reads in flight, then 64 FMAs
-                float4 dv[4], wv[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int e = min(eb + u, ne - 1);
-                    dv[u] = *reinterpret_cast<const float4*>(dls + (e0 + e) * LD + ty * 4);
-                    wv[u] = *reinterpret_cast<const float4*>(wgs + e * LD + tx * 4);
-                    if (eb + u >= ne) wv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const float dd[4] = {dv[u].x, dv[u].y, dv[u].z, dv[u].w};
-                    const float ww[4] = {wv[u].x, wv[u].y, wv[u].z, wv[u].w};
-#pragma unroll
-                    for (int a = 0; a < 4; ++a)
-#pragma unroll
-                        for (int b = 0; b < 4; ++b) acc[a][b] = fmaf(dd[a], ww[b], acc[a][b]);
-                }
-            }
+            for (int s_ = 0; s_ < 16; ++s_)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(afr[s_], bfr[HOIST ? eb : 0][s_], acc, 0, 0, 0);
         }
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {   // stores beyond T or d are dropped by the range check
-            float cur[4];
-            Vec4io<T>::unpack(cur_raw[a], cur);
+        for (int q = 0; q < NCH; ++q) {   // stores beyond T or d are dropped by the range check
 #pragma unroll
-            for (int b = 0; b < 4; ++b) cur[b] += acc[a][b];
-            Vec4buf<T>::store(rs_dx, i < d ? (uint32_t)(((ty * 4 + a) * d + i) * sizeof(T)) : BUF_OOB,
-                                 Vec4io<T>::pack(cur));
+            for (int j = 0; j < CN; ++j) cur[q][j] += acc[q * CN + j];
+            BufChunk<T>::store(rs_dx, c0 + q * CN < d ? (uint32_t)((r * d + c0 + q * CN) * sizeof(T)) : BUF_OOB, cur[q]);
         }
     }
 }
@@ -399,13 +365,13 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
     const int n = s->d_model * s->E;
     gate_dwg_reduce_kernel<<<ceil_div(n, 256), 256, 0, st>>>(n, nch_used, partial, dWg);
     if (dx) {
-        const size_t smem = ((size_t)s->E + (s->E < 64 ? s->E : 64)) * (GX_TB + 4) * 4;
-        if (smem > 64 * 1024) {   // opt in to more than 64 KB of LDS (E > 128)
-            static const hipError_t attr = hipFuncSetAttribute(
-                (const void*)gate_dx_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-            (void)attr;
-        }
-        gate_dx_kernel<T><<<ceil_div(s->T, GX_TB), 256, smem, st>>>(s->T, s->d_model, s->E, dlogits, Wg, (T*)dx);
+        const int grid_dx = ceil_div(s->T, 32);
+#define GDX(EB, VEC) gate_dx_kernel<T, EB, VEC><<<grid_dx, 512, 0, st>>>(s->T, s->d_model, s->E, dlogits, Wg, (T*)dx)
+#define GDXE(VEC) do { if (s->E <= 32) GDX(1, VEC); else if (s->E <= 64) GDX(2, VEC); \
+                       else if (s->E <= 128) GDX(4, VEC); else GDX(8, VEC); } while (0)
+        if (s->E % 4 == 0) GDXE(true); else GDXE(false);
+#undef GDXE
+#undef GDX
     }
 }
 

@@ -102,13 +102,24 @@ __device__ __forceinline__ float buf_load_f32(__amdgpu_buffer_rsrc_t r, uint32_t
 // 16 bytes of activations at byte offset off, widened to fp32
 template <typename T> struct BufChunk;
 template <> struct BufChunk<float> {
+    static constexpr int N = 4;
     __device__ static __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t off, float (&v)[4]) {
         const u32x4_buf_t q = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(q[i]);
     }
+    __device__ static __forceinline__ void store(__amdgpu_buffer_rsrc_t r, uint32_t off, const float (&v)[4]) {
+        const u32x4_buf_t q = {__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])};
+        __builtin_amdgcn_raw_buffer_store_b128(q, r, off, 0, 0);
+    }
 };
 template <> struct BufChunk<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void store(__amdgpu_buffer_rsrc_t r, uint32_t off, const float (&v)[8]) {
+        const u32x4_buf_t q = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]), pack_bf16x2(v[4], v[5]),
+                               pack_bf16x2(v[6], v[7])};
+        __builtin_amdgcn_raw_buffer_store_b128(q, r, off, 0, 0);
+    }
     __device__ static __forceinline__ void load(__amdgpu_buffer_rsrc_t r, uint32_t off, float (&v)[8]) {
         const u32x4_buf_t q = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
 #pragma unroll
