@@ -161,14 +161,21 @@ extern "C" int moe_gate_bwd(const moe_shape* shape, const float* dgate_w, const 
 }
 
 // ---------------------------------------------------------------------------
-// dWg[d,E] = x^T dlogits : partial sums over token chunks, then an ordered sum
+// dWg[d,E] = x^T dlogits   on the fp32 matrix pipe: partial sums over token
+// chunks, then an ordered sum over the chunks.
+// Workgroup: 256 columns of d x 32 experts x one chunk of tokens, 4 waves that
+// split the chunk's tokens.  The reduction runs over tokens, two per MFMA (one
+// per lane half).  A lane loads 8 consecutive columns of its token (16 bytes for
+// bf16) and feeds them to 8 MFMAs: in MFMA c, tile row m stands for column
+// i0 + 8m + c, so the 8 accumulator tiles cover 256 columns and every load is a
+// contiguous 512-byte piece of a token row.  B = the token's dlogits row.
 // ---------------------------------------------------------------------------
-#define GW_DT 64   // d columns per workgroup
-#define GW_TT 64   // tokens per LDS slab
+#define GW_COLS 256
+#define GW_WAVES 4
 
 static inline int gw_chunks(const moe_shape* s) {
-    // enough workgroups to fill the chip, at least 256 tokens per chunk
-    int want = ceil_div(1024, ceil_div(s->d_model, GW_DT));
+    // enough workgroups to fill the chip twice, at least 256 tokens per chunk
+    int want = ceil_div(512, ceil_div(s->d_model, GW_COLS) * ceil_div(s->E, 32));
     int maxc = ceil_div(s->T, 256);
     int n = want < maxc ? want : maxc;
     // one chunk's rows of x are addressed with 32-bit byte offsets: keep it below 1 GiB
@@ -176,89 +183,76 @@ static inline int gw_chunks(const moe_shape* s) {
     if (n < minc) n = minc;
     return n < 1 ? 1 : n;
 }
+// tokens per chunk: a multiple of 2 tokens per wave
+static inline int gw_chunk_tokens(const moe_shape* s) {
+    return ceil_div(ceil_div(s->T, gw_chunks(s)), 2 * GW_WAVES) * 2 * GW_WAVES;
+}
 size_t gate_logits_bwd_ws_bytes(const moe_shape* s) {
-    return align_up((size_t)gw_chunks(s) * s->d_model * s->E * 4, 256);
+    return align_up((size_t)ceil_div(s->T, gw_chunk_tokens(s)) * s->d_model * s->E * 4, 256);
 }
 
-// Workgroup: 64 columns of d x one chunk of tokens; experts in passes of 32.
-// Thread (ti,te) owns a 4-column x 2-expert register tile.
 template <typename T>
-__global__ __launch_bounds__(256) void gate_dwg_partial_kernel(
+__global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
     int Tn, int d, int E, int tok_per_chunk, const T* __restrict__ x,
     const float* __restrict__ dlogits, float* __restrict__ partial) {
-    __shared__ __align__(16) float xs[GW_TT][GW_DT];
-    __shared__ __align__(16) float dls[GW_TT][32];
-    const int tid = threadIdx.x, ti = tid & 15, te = tid >> 4;
-    const int i0 = blockIdx.x * GW_DT;
+    extern __shared__ __align__(16) float gw_red[];      // [wave][256 columns][32 experts]
+    constexpr int GRP = sizeof(T) == 2 ? 8 : 4;          // token pairs whose loads are in flight together
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int i0 = blockIdx.x * GW_COLS, e0 = blockIdx.z * 32;
     const int tbeg = blockIdx.y * tok_per_chunk;
     const int tend = min(Tn, tbeg + tok_per_chunk);
-    constexpr int CN = Chunk<T>::N, CPR = GW_DT / CN;
+    const int per_wave = tok_per_chunk / GW_WAVES;
+    const int w_lo = tbeg + wave * per_wave, w_hi = min(tend, w_lo + per_wave);
     const int nrows = max(tend - tbeg, 0);
     const __amdgpu_buffer_rsrc_t rs_x = buf_rsrc(x + (size_t)tbeg * d, (size_t)nrows * d * sizeof(T));
     const __amdgpu_buffer_rsrc_t rs_d = buf_rsrc(dlogits + (size_t)tbeg * E, (size_t)nrows * E * 4);
-    constexpr int XPT = GW_TT * CPR / 256 > 0 ? GW_TT * CPR / 256 : 1;
-    constexpr int DPT = GW_TT * 32 / 256;
-    for (int e0 = 0; e0 < E; e0 += 32) {
-        float acc[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
-        float xr[XPT][CN], dr[DPT];
-        auto fetch = [&](int ts) {   // branch free: out-of-range lanes read zeros
+    const int col = i0 + 8 * r;
+    const bool col_ok = col < d, e_ok = e0 + r < E;      // d % 8 == 0: 8 columns are inside or wholly beyond
+    glm_f32x16 acc[8];
 #pragma unroll
-            for (int j = 0; j < XPT; ++j) {
-                const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
-                const bool ok = c < GW_TT * CPR && i0 + cc * CN < d;   // rows beyond tend fall outside rs_x
-                BufChunk<T>::load(rs_x, ok ? (uint32_t)(((ts - tbeg + r) * d + i0 + cc * CN) * sizeof(T)) : BUF_OOB, xr[j]);
-            }
+    for (int c = 0; c < 8; ++c)
 #pragma unroll
-            for (int j = 0; j < DPT; ++j) {
-                const int c = tid + j * 256, r = c >> 5, e = c & 31;
-                const bool ok = e0 + e < E;
-                dr[j] = buf_load_f32(rs_d, ok ? (uint32_t)(((ts - tbeg + r) * E + e0 + e) * 4) : BUF_OOB);
-            }
-        };
-        fetch(tbeg);
-        for (int ts = tbeg; ts < tend; ts += GW_TT) {
-            __syncthreads();
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.0f;
+    // two register buffers: the loads of the next group travel under this group's MFMAs
+    float a[2][GRP][8], b[2][GRP];
+    auto fetch = [&](int t, float (&fa)[GRP][8], float (&fb)[GRP]) {
 #pragma unroll
-            for (int j = 0; j < XPT; ++j) {
-                const int c = tid + j * 256, r = c / CPR, cc = c - r * CPR;
-                if (c < GW_TT * CPR) {
-#pragma unroll
-                    for (int q = 0; q < CN; ++q) xs[r][cc * CN + q] = xr[j][q];
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < DPT; ++j) {
-                const int c = tid + j * 256;
-                dls[c >> 5][c & 31] = dr[j];
-            }
-            __syncthreads();
-            if (ts + GW_TT < tend) fetch(ts + GW_TT);
-            for (int tb = 0; tb < GW_TT; tb += 8) {   // 16 LDS reads in flight, then 64 FMAs
-                float4 xv[8];
-                float2 dv[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    xv[u] = *reinterpret_cast<const float4*>(&xs[tb + u][ti * 4]);
-                    dv[u] = *reinterpret_cast<const float2*>(&dls[tb + u][te * 2]);
-                }
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    acc[0][0] = fmaf(xv[u].x, dv[u].x, acc[0][0]); acc[0][1] = fmaf(xv[u].x, dv[u].y, acc[0][1]);
-                    acc[1][0] = fmaf(xv[u].y, dv[u].x, acc[1][0]); acc[1][1] = fmaf(xv[u].y, dv[u].y, acc[1][1]);
-                    acc[2][0] = fmaf(xv[u].z, dv[u].x, acc[2][0]); acc[2][1] = fmaf(xv[u].z, dv[u].y, acc[2][1]);
-                    acc[3][0] = fmaf(xv[u].w, dv[u].x, acc[3][0]); acc[3][1] = fmaf(xv[u].w, dv[u].y, acc[3][1]);
-                }
-            }
+        for (int u = 0; u < GRP; ++u) {
+            const int tok = t + 2 * u + h;
+            const bool ok = tok < w_hi;                  // the next wave's tokens are not ours
+            load8<T>(rs_x, ok && col_ok ? (uint32_t)(((tok - tbeg) * d + col) * sizeof(T)) : BUF_OOB, fa[u]);
+            fb[u] = buf_load_f32(rs_d, ok && e_ok ? (uint32_t)(((tok - tbeg) * E + e0 + r) * 4) : BUF_OOB);
         }
+    };
+    auto multiply = [&](const float (&fa)[GRP][8], const float (&fb)[GRP]) {
 #pragma unroll
-        for (int a = 0; a < 4; ++a) {
-            const int i = i0 + ti * 4 + a;
-            if (i >= d) continue;
-            float* out = partial + ((size_t)blockIdx.y * d + i) * E;
+        for (int u = 0; u < GRP; ++u)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
-                if (e0 + te * 2 + b < E) out[e0 + te * 2 + b] = acc[a][b];
+            for (int c = 0; c < 8; ++c) acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[u][c], fb[u], acc[c], 0, 0, 0);
+    };
+    fetch(w_lo, a[0], b[0]);
+    for (int t = w_lo; t < w_hi; t += 4 * GRP) {
+        fetch(t + 2 * GRP, a[1], b[1]);      // beyond w_hi: every lane reads zeros, harmless
+        multiply(a[0], b[0]);
+        fetch(t + 4 * GRP, a[0], b[0]);
+        multiply(a[1], b[1]);
+    }
+    // accumulator v of tile c, lane l: column i0 + 8*(8*(v/4) + 4*(l/32) + v%4) + c, expert e0 + l%32
+#pragma unroll
+    for (int c = 0; c < 8; ++c)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int m = 8 * (v >> 2) + 4 * h + (v & 3);
+            gw_red[(wave * GW_COLS + 8 * m + c) * 32 + r] = acc[c][v];
         }
+    __syncthreads();
+    for (int o = threadIdx.x; o < GW_COLS * 32; o += 64 * GW_WAVES) {
+        const int il = o >> 5, e = o & 31;
+        float sum = 0.0f;
+#pragma unroll
+        for (int w = 0; w < GW_WAVES; ++w) sum += gw_red[(w * GW_COLS + il) * 32 + e];
+        if (i0 + il < d && e0 + e < E) partial[((size_t)blockIdx.y * d + i0 + il) * E + e0 + e] = sum;
     }
 }
 
@@ -268,7 +262,15 @@ __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(int n, int nchunk,
     const int idx = blockIdx.x * 256 + threadIdx.x;
     if (idx >= n) return;
     float s = 0.0f;
-    for (int c = 0; c < nchunk; ++c) s += partial[(size_t)c * n + idx];
+    int c = 0;
+    for (; c + 8 <= nchunk; c += 8) {   // 8 independent loads in flight, added in chunk order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(c + u) * n + idx];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; c < nchunk; ++c) s += partial[(size_t)c * n + idx];
     dWg[idx] = s;
 }
 
@@ -357,11 +359,15 @@ template <typename T>
 static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const float* Wg,
                                    const float* dlogits, float* dWg, void* dx, float* partial,
                                    hipStream_t st) {
-    const int nch = gw_chunks(s);
-    const int tpc = ceil_div(ceil_div(s->T, nch), GW_TT) * GW_TT;
+    const int tpc = gw_chunk_tokens(s);
     const int nch_used = ceil_div(s->T, tpc);
-    dim3 grid(ceil_div(s->d_model, GW_DT), nch_used);
-    gate_dwg_partial_kernel<T><<<grid, 256, 0, st>>>(s->T, s->d_model, s->E, tpc, (const T*)x, dlogits, partial);
+    dim3 grid(ceil_div(s->d_model, GW_COLS), nch_used, ceil_div(s->E, 32));
+    constexpr size_t red_bytes = (size_t)GW_WAVES * GW_COLS * 32 * sizeof(float);   // 128 KB: opt in beyond 64 KB
+    static const hipError_t attr = hipFuncSetAttribute(
+        (const void*)gate_dwg_partial_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)red_bytes);
+    (void)attr;
+    gate_dwg_partial_kernel<T><<<grid, 64 * GW_WAVES, red_bytes, st>>>(s->T, s->d_model, s->E, tpc, (const T*)x,
+                                                                      dlogits, partial);
     const int n = s->d_model * s->E;
     gate_dwg_reduce_kernel<<<ceil_div(n, 256), 256, 0, st>>>(n, nch_used, partial, dWg);
     if (dx) {
