@@ -52,6 +52,63 @@ _F = np.float64
 
 
 # --------------------------------------------------------------------------
+# seeded noise: gate jitter (Sec. 5.1) and expert dropout (Sec. 5.4)
+# --------------------------------------------------------------------------
+# Both sides of a parity test must draw the same random numbers, so they come
+# from a counter-based generator that each implements for itself: Philox4x32
+# with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy
+# as 1, 2, 3", SC 2011).  Element i of a tensor uses word i % 4 of the block with
+# counter (i // 4 low word, i // 4 high word, stream, 0) and key (seed low word,
+# seed high word); stream 1 = gate jitter, stream 2 = expert dropout.
+_PHILOX_M0, _PHILOX_M1 = 0xD2511F53, 0xCD9E8D57
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+STREAM_JITTER, STREAM_DROPOUT = 1, 2
+
+
+def philox4x32(c0, c1, c2, c3, k0, k1, rounds=10):
+    """One Philox4x32 block per counter (arrays of 32-bit words held in uint64);
+    returns the four 32-bit output words."""
+    m32 = np.uint64(0xFFFFFFFF)
+    c0, c1, c2, c3 = (np.asarray(v, np.uint64) & m32 for v in (c0, c1, c2, c3))
+    k0, k1 = np.uint64(k0) & m32, np.uint64(k1) & m32
+    for _ in range(rounds):
+        p0 = np.uint64(_PHILOX_M0) * c0             # 32 x 32 -> 64 bit products
+        p1 = np.uint64(_PHILOX_M1) * c2
+        c0, c1, c2, c3 = ((p1 >> np.uint64(32)) ^ c1 ^ k0) & m32, p1 & m32, \
+                         ((p0 >> np.uint64(32)) ^ c3 ^ k1) & m32, p0 & m32
+        k0 = (k0 + np.uint64(_PHILOX_W0)) & m32
+        k1 = (k1 + np.uint64(_PHILOX_W1)) & m32
+    return c0, c1, c2, c3
+
+
+def random_words(n, seed, stream):
+    """The 32-bit word of elements 0..n-1 (as uint64 array) under the layout above."""
+    blocks = np.arange((n + 3) // 4, dtype=np.uint64)
+    w = philox4x32(blocks & np.uint64(0xFFFFFFFF), blocks >> np.uint64(32), stream, 0,
+                   int(seed) & 0xFFFFFFFF, (int(seed) >> 32) & 0xFFFFFFFF)
+    return np.stack(w, axis=1).reshape(-1)[:n]
+
+
+def jitter_noise(T, d, eps, seed):
+    """Multiplicative jitter on the gate's input (Sec. 5.1: jittering noise on the
+    gating input, as in the Switch Transformer): factor 1 + eps (2u - 1) per
+    element of x, u = word / 2^32 uniform in [0,1).  Only the gate sees x * noise;
+    the experts receive x itself."""
+    u = random_words(T * d, seed, STREAM_JITTER).astype(_F) / 4294967296.0
+    return (1.0 + eps * (2.0 * u - 1.0)).reshape(T, d)
+
+
+def dropout_scale(E, C, f, p, seed):
+    """Expert dropout (Sec. 5.4: expert dropout of 0.4 in fine-tuning, as in the
+    Switch Transformer): dropout on the expert's hidden activation.  Element
+    (e, s, c) of the [E, C, f] buffer is dropped when its word < floor(p 2^32);
+    kept elements are scaled by 1 / (1 - p).  Returns the scale tensor."""
+    w = random_words(E * C * f, seed, STREAM_DROPOUT)
+    keep = w >= np.uint64(int(math.floor(p * 4294967296.0)))
+    return (keep.astype(_F) / (1.0 - p)).reshape(E, C, f)
+
+
+# --------------------------------------------------------------------------
 # gate: projection, softmax, top-k, weights          (Sec. 3.2, Sec. 5.1)
 # --------------------------------------------------------------------------
 def gate_logits(x, Wg, bias=None):
@@ -256,9 +313,10 @@ def act_grad(z, kind):
     raise ValueError(kind)
 
 
-def expert_ffn_fwd(Xd, expert_count, W1, W2, kind):
+def expert_ffn_fwd(Xd, expert_count, W1, W2, kind, scale=None):
     """Per expert e, on its first n_e = expert_count[e] rows only:
-    Z = Xd_e W1_e, H = act(Z), Yd_e = H W2_e.  No biases.  Other rows stay 0."""
+    Z = Xd_e W1_e, H = act(Z), Yd_e = H W2_e.  No biases.  Other rows stay 0.
+    scale[E,C,f] (expert dropout, see dropout_scale): H = act(Z) * scale."""
     Xd = np.asarray(Xd, _F)
     E, C, d = Xd.shape
     f = W1.shape[2]
@@ -271,14 +329,17 @@ def expert_ffn_fwd(Xd, expert_count, W1, W2, kind):
             continue
         Z[e, :n] = Xd[e, :n] @ np.asarray(W1[e], _F)
         H[e, :n] = act(Z[e, :n], kind)
+        if scale is not None:
+            H[e, :n] *= scale[e, :n]
         Yd[e, :n] = H[e, :n] @ np.asarray(W2[e], _F)
     return Z, H, Yd
 
 
-def expert_ffn_bwd(dYd, Xd, Z, expert_count, W1, W2, kind):
+def expert_ffn_bwd(dYd, Xd, Z, expert_count, W1, W2, kind, scale=None):
     """dH = dYd W2^T, dZ = dH * act'(Z), dW2 = H^T dYd, dXd = dZ W1^T,
     dW1 = Xd^T dZ, each over the first n_e rows of expert e; an empty expert
-    gets zero weight gradients."""
+    gets zero weight gradients.  With expert dropout (scale, a constant of the
+    step) H = act(Z) * scale and dZ = dH * scale * act'(Z)."""
     dYd = np.asarray(dYd, _F)
     Xd = np.asarray(Xd, _F)
     Z = np.asarray(Z, _F)
@@ -295,6 +356,9 @@ def expert_ffn_bwd(dYd, Xd, Z, expert_count, W1, W2, kind):
         H = act(Z[e, :n], kind)
         dH = dYd[e, :n] @ w2.T
         dZ = dH * act_grad(Z[e, :n], kind)
+        if scale is not None:
+            H = H * scale[e, :n]
+            dZ = dZ * scale[e, :n]
         dW2[e] = H.T @ dYd[e, :n]
         dXd[e, :n] = dZ @ w1.T
         dW1[e] = Xd[e, :n].T @ dZ
@@ -384,7 +448,8 @@ def gate_logits_bwd(x, Wg, dlogits):
 # --------------------------------------------------------------------------
 # the whole layer, forward and backward
 # --------------------------------------------------------------------------
-def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None, aux_coef=0.0, groups=1):
+def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None, aux_coef=0.0, groups=1,
+              jitter_eps=0.0, drop_p=0.0, seed=0):
     """One MoE layer forward and backward in the order gate -> capacity/RTS ->
     dispatch -> experts -> combine, then the reverse.  `logits`, when given,
     replaces the gate projection as the routing input (used to route on the
@@ -392,9 +457,15 @@ def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None, aux_co
     backward still uses x and Wg.  aux_coef > 0 adds aux_coef * (balancing loss)
     to the objective: its value is returned and its gradient joins dlogits.
     groups > 1 selects tokens inside groups of T/groups consecutive tokens.
+    jitter_eps > 0 multiplies the gate's input by jitter_noise(seed); drop_p > 0
+    applies expert dropout with dropout_scale(seed).
     Returns a dict of every intermediate."""
     E = W1.shape[0]
-    lg = gate_logits(x, Wg, bias) if logits is None else np.asarray(logits, _F)
+    xg = np.asarray(x, _F)                       # what the gate sees
+    if jitter_eps != 0.0:
+        xg = xg * jitter_noise(xg.shape[0], xg.shape[1], jitter_eps, seed)
+    scale = dropout_scale(E, C, W1.shape[2], drop_p, seed) if drop_p != 0.0 else None
+    lg = gate_logits(xg, Wg, bias) if logits is None else np.asarray(logits, _F)
     p = softmax(lg)
     eidx = top_k(lg, k)
     g = gate_weights(p, eidx)
@@ -403,7 +474,7 @@ def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None, aux_co
     else:
         slot, count, demand, slot_src = route_grouped(eidx, rts_keys, E, C, groups)
     Xd = dispatch(x, slot_src, k)
-    Z, H, Yd = expert_ffn_fwd(Xd, count, W1, W2, kind)
+    Z, H, Yd = expert_ffn_fwd(Xd, count, W1, W2, kind, scale)
     y = combine_fwd(Yd, eidx, slot, g)
     out = dict(logits=lg, probs=p, expert_idx=eidx, gate_w=g, slot=slot,
                expert_count=count, expert_demand=demand, slot_src=slot_src,
@@ -413,12 +484,14 @@ def moe_layer(x, Wg, bias, W1, W2, rts_keys, dy, k, C, kind, logits=None, aux_co
     if dy is None:
         return out
     dYd, dg = combine_bwd(dy, Yd, eidx, slot, g)
-    dXd, dW1, dW2 = expert_ffn_bwd(dYd, Xd, Z, count, W1, W2, kind)
+    dXd, dW1, dW2 = expert_ffn_bwd(dYd, Xd, Z, count, W1, W2, kind, scale)
     dx_disp = combine_fwd(dXd, eidx, slot, None)
     dl = gate_bwd(dg, p, eidx, slot)
     if aux_coef != 0.0:
         dl = dl + aux_loss_bwd(p, f, aux_coef)
-    dWg, dx_gate = gate_logits_bwd(x, Wg, dl)
+    dWg, dx_gate = gate_logits_bwd(xg, Wg, dl)   # dWg = (x * noise)^T dl
+    if jitter_eps != 0.0:
+        dx_gate = dx_gate * jitter_noise(xg.shape[0], xg.shape[1], jitter_eps, seed)
     out.update(dYd=dYd, dgate_w=dg, dXd=dXd, dW1=dW1, dW2=dW2, dx_disp=dx_disp,
                dlogits=dl, dWg=dWg, dx=dx_disp + dx_gate)
     return out
