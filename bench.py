@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--aux-coef", type=float, default=0.0,
                     help="weight of the balancing auxiliary loss (Sec. 5.1 uses 0.01); 0 = the plain hot path")
+    ap.add_argument("--jitter-eps", type=float, default=0.0, help="gate jitter (Sec. 5.1, Switch: 0.01); 0 = off")
+    ap.add_argument("--drop-p", type=float, default=0.0, help="expert dropout (Sec. 5.4: 0.4 in fine-tuning); 0 = off")
     ap.add_argument("--groups", type=int, default=1,
                     help="grouped token selection inside groups of T/groups consecutive tokens (Sec. 3.1); 1 = plain")
     ap.add_argument("--forward-only", action="store_true",
@@ -100,12 +102,15 @@ def main():
     L = layer
 
     calls = [
-        ("gate_logits", lambda: B.moe_gate_logits(s, x, Wg, bias, L.logits)),
+        ("gate_logits", lambda: B.moe_gate_logits_jitter(s, x, Wg, bias, args.jitter_eps, 7, L.logits)),
         ("gate_route", lambda: B.moe_gate_route_grouped(s, args.groups, L.logits, keys, L.probs, L.expert_idx,
                                                         L.gate_w, L.slot, L.expert_count, L.expert_demand,
                                                         L.slot_src, L.ws)),
         ("dispatch", lambda: B.moe_dispatch(s, x, L.slot_src, L.expert_count, L.xd)),
-        ("expert_ffn_fwd", lambda: B.moe_expert_ffn_fwd(s, L.xd, L.expert_count, W1, W2, L.h, L.dact, L.yd)),
+        ("expert_ffn_fwd", (lambda: B.moe_expert_ffn_fwd_dropout(s, L.xd, L.expert_count, W1, W2, args.drop_p, 7,
+                                                                 L.h, L.dact, L.yd))
+         if args.drop_p > 0 else
+         (lambda: B.moe_expert_ffn_fwd(s, L.xd, L.expert_count, W1, W2, L.h, L.dact, L.yd))),
         ("combine_fwd", lambda: B.moe_combine_fwd(s, L.yd, L.expert_idx, L.slot, L.gate_w, L.y)),
         ("combine_bwd", lambda: B.moe_combine_bwd(s, dy, L.yd, L.expert_idx, L.slot, L.gate_w, L.dyd, L.dgate_w)),
         ("expert_ffn_bwd", lambda: B.moe_expert_ffn_bwd(s, L.dyd, L.xd, L.h, L.dact, L.expert_count, W1, W2,
@@ -115,7 +120,8 @@ def main():
          if args.aux_coef == 0.0 else
          (lambda: B.moe_gate_bwd_aux(s, L.dgate_w, L.probs, L.expert_idx, L.slot, L.first_frac, args.aux_coef,
                                      L.dlogits))),
-        ("gate_logits_bwd", lambda: B.moe_gate_logits_bwd(s, x, Wg, L.dlogits, L.dWg, L.dx, L.ws)),
+        ("gate_logits_bwd", lambda: B.moe_gate_logits_bwd_jitter(s, x, Wg, L.dlogits, args.jitter_eps, 7, L.dWg,
+                                                                 L.dx, L.ws)),
     ]
     if args.aux_coef != 0.0 and not args.forward_only:
         calls.insert(2, ("aux_loss", lambda: B.moe_aux_loss(s, L.probs, L.expert_idx, L.first_frac, L.mean_prob,
@@ -226,7 +232,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "T": w.T, "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k,
                    "capacity": w.capacity, "capacity_factor": w.capacity_factor,
-                   "act": "gelu" if w.act == I.GELU else "relu", "aux_coef": args.aux_coef, "groups": args.groups,
+                   "act": "gelu" if w.act == I.GELU else "relu", "aux_coef": args.aux_coef, "groups": args.groups, "jitter_eps": args.jitter_eps,
+                   "drop_p": args.drop_p,
                    "mode": "forward-only (evaluation)" if args.forward_only else "forward+backward (training)",
                    "kept_assignments": M,
                    "expert_demand_max": int(L.expert_demand.max().item()),

@@ -35,6 +35,12 @@
  *  - Return value: MOE_OK (0) or a negative moe_status.  Argument errors are
  *    detected on the host before anything is enqueued, so outputs are
  *    untouched.  Non-finite logits or keys give undefined routing (no fault).
+ *  - Seeded noise (gate jitter, expert dropout) comes from the counter-based
+ *    generator Philox4x32 with 10 rounds (Salmon et al., SC 2011), so a caller or
+ *    a checker can reproduce every draw: element i of a tensor uses output word
+ *    i % 4 of the block with counter (i/4 low word, i/4 high word, stream, 0) and
+ *    key (seed low word, seed high word); stream 1 = gate jitter, indexed over
+ *    x[T, d_model]; stream 2 = expert dropout, indexed over h[E, C, d_ff].
  *  - Shape limits: T, d_model, d_ff, E, capacity >= 1; k in {1,2}; E >= k;
  *    E <= 256; d_model and d_ff multiples of 8; T*k and E*capacity < 2^30.
  */
@@ -88,6 +94,15 @@ size_t moe_workspace_bytes(const moe_shape* shape);
  * no bias. */
 int moe_gate_logits(const moe_shape* shape, const void* x, const float* Wg,
                     const float* bias_or_null, float* logits, void* stream);
+
+/* Gate projection with jitter (Sec. 5.1: jittering noise on the gating input,
+ * as in the Switch Transformer):  logits = (x .* noise) * Wg (+ bias) with
+ * noise[t,i] = 1 + jitter_eps * (2u - 1), u = word / 2^32 in [0,1).  Only the
+ * gate sees the noise; dispatch copies x itself.  0 <= jitter_eps < 1;
+ * jitter_eps = 0 is moe_gate_logits. */
+int moe_gate_logits_jitter(const moe_shape* shape, const void* x, const float* Wg,
+                           const float* bias_or_null, float jitter_eps, uint64_t seed,
+                           float* logits, void* stream);
 
 /* Gate + capacity assignment (Sec. 5.1 top-1 / top-2 gating; Sec. 3.1 expert
  * capacity and Random Token Selection).
@@ -158,6 +173,17 @@ int moe_expert_ffn_fwd(const moe_shape* shape, const void* xd, const int32_t* ex
 int moe_utilisation_accumulate(const moe_shape* shape, const int32_t* counts, int64_t* accum,
                                void* stream);
 
+/* Expert FFN forward with expert dropout (Sec. 5.4: expert dropout of 0.4 in
+ * fine-tuning, as in the Switch Transformer: dropout on the expert's hidden
+ * activation).  As moe_expert_ffn_fwd, except that element (e, s, c) of h is
+ * dropped when its noise word < floor(drop_p * 2^32) and kept elements are
+ * scaled by 1 / (1 - drop_p).  The same factor is folded into dact_saved, so
+ * moe_expert_ffn_bwd is used unchanged.  0 <= drop_p < 1; drop_p = 0 is
+ * moe_expert_ffn_fwd; dact_saved is required. */
+int moe_expert_ffn_fwd_dropout(const moe_shape* shape, const void* xd, const int32_t* expert_count,
+                               const void* W1, const void* W2, float drop_p, uint64_t seed,
+                               void* h_saved, void* dact_saved, void* yd, void* stream);
+
 /* Combine (the mixture itself; a token dropped by every chosen expert gets a
  * zero row and is carried by the residual connection around the layer,
  * Sec. 4.2 / Sec. 3.1):
@@ -219,6 +245,12 @@ int moe_gate_bwd_aux(const moe_shape* shape, const float* dgate_w, const float* 
 int moe_gate_logits_bwd(const moe_shape* shape, const void* x, const float* Wg,
                         const float* dlogits, float* dWg, void* dx_accum,
                         void* ws, size_t ws_bytes, void* stream);
+
+/* Backward of moe_gate_logits_jitter (same jitter_eps and seed as the forward):
+ *   dWg = (x .* noise)^T * dlogits,   dx_accum += (dlogits * Wg^T) .* noise. */
+int moe_gate_logits_bwd_jitter(const moe_shape* shape, const void* x, const float* Wg,
+                               const float* dlogits, float jitter_eps, uint64_t seed, float* dWg,
+                               void* dx_accum, void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

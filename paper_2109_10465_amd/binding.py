@@ -19,6 +19,7 @@ EXPORTS = [
     "moe_dispatch", "moe_expert_ffn_fwd", "moe_combine_fwd", "moe_combine_bwd", "moe_expert_ffn_bwd",
     "moe_gate_bwd", "moe_gate_logits_bwd", "moe_aux_loss", "moe_gate_bwd_aux",
     "moe_utilisation_accumulate", "moe_gate_route_grouped",
+    "moe_gate_logits_jitter", "moe_gate_logits_bwd_jitter", "moe_expert_ffn_fwd_dropout",
 ]
 
 
@@ -66,6 +67,9 @@ def lib():
             "moe_gate_bwd_aux": [shp] + [vp] * 5 + [ctypes.c_float, vp, vp],
             "moe_utilisation_accumulate": [shp, vp, vp, vp],
             "moe_gate_route_grouped": [shp, i32] + [vp] * 10 + [sz, vp],
+            "moe_gate_logits_jitter": [shp, vp, vp, vp, ctypes.c_float, ctypes.c_uint64, vp, vp],
+            "moe_gate_logits_bwd_jitter": [shp, vp, vp, vp, ctypes.c_float, ctypes.c_uint64, vp, vp, vp, sz, vp],
+            "moe_expert_ffn_fwd_dropout": [shp] + [vp] * 4 + [ctypes.c_float, ctypes.c_uint64] + [vp] * 4,
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -175,6 +179,25 @@ def moe_gate_bwd_aux(shape, dgate_w, probs, expert_idx, slot, first_frac, aux_co
     _check(lib().moe_gate_bwd_aux(ctypes.byref(shape), _p(dgate_w), _p(probs), _p(expert_idx), _p(slot),
                                   _p(first_frac), float(aux_coef), _p(dlogits), _stream(stream)),
            "moe_gate_bwd_aux")
+
+
+def moe_gate_logits_jitter(shape, x, Wg, bias, jitter_eps, seed, logits, stream=None):
+    _check(lib().moe_gate_logits_jitter(ctypes.byref(shape), _p(x), _p(Wg), _p(bias), float(jitter_eps), int(seed),
+                                        _p(logits), _stream(stream)), "moe_gate_logits_jitter")
+
+
+def moe_gate_logits_bwd_jitter(shape, x, Wg, dlogits, jitter_eps, seed, dWg, dx_accum, ws, stream=None):
+    _check(lib().moe_gate_logits_bwd_jitter(ctypes.byref(shape), _p(x), _p(Wg), _p(dlogits), float(jitter_eps),
+                                            int(seed), _p(dWg), _p(dx_accum), _p(ws),
+                                            0 if ws is None else ws.numel() * ws.element_size(),
+                                            _stream(stream)), "moe_gate_logits_bwd_jitter")
+
+
+def moe_expert_ffn_fwd_dropout(shape, xd, expert_count, W1, W2, drop_p, seed, h_saved, dact_saved, yd,
+                               stream=None):
+    _check(lib().moe_expert_ffn_fwd_dropout(ctypes.byref(shape), _p(xd), _p(expert_count), _p(W1), _p(W2),
+                                            float(drop_p), int(seed), _p(h_saved), _p(dact_saved), _p(yd),
+                                            _stream(stream)), "moe_expert_ffn_fwd_dropout")
 
 
 def moe_utilisation_accumulate(shape, counts, accum, stream=None):

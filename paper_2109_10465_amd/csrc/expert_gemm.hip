@@ -39,6 +39,7 @@
 //     derivative are evaluated once, in the forward epilogue (code kept in a
 //     rolled loop), and the backward epilogue only multiplies by the saved
 //     derivative, which it fetched into registers before the main loop.
+#include <math.h>
 #include "moe_common.h"
 
 // bf16 tile shape (tuning knobs; the defaults are the shipped configuration)
@@ -70,6 +71,11 @@ struct GemmArgs {
     int M, N, K;      // extents; the one bounded by expert_count is an upper limit
     int var_k;        // 0: rows (M) bounded by expert_count; 1: K bounded by it
     int tiles_m, tiles_n, E;
+    // expert dropout in the activation epilogue (drop_thr = 0: off): an element is dropped when its
+    // noise word < drop_thr, kept ones are scaled by drop_scale = 1 / (1 - p)
+    uint32_t drop_thr;
+    float drop_scale;
+    uint64_t seed;
 };
 
 template <typename T> struct Mma;
@@ -262,6 +268,16 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& p, size_t o, float (&v
         float h[4], a[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) act_both<sizeof(T) == 2, ACT>(v[i], h[i], a[i]);
+        if (p.drop_thr) {   // expert dropout (Sec. 5.4): o is the element index in [E, C, d_ff], a multiple of 4
+            uint32_t w[4];
+            noise_words(o, MOE_STREAM_DROPOUT, p.seed, w);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float sc = w[i] >= p.drop_thr ? p.drop_scale : 0.0f;
+                h[i] *= sc;     // the mask rides in the saved derivative too, so the
+                a[i] *= sc;     // backward needs no knowledge of it
+            }
+        }
         *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(a);
         *reinterpret_cast<raw*>((T*)p.out1 + o) = Vec4io<T>::pack(h);
     } else if constexpr (EPI == EPI_H) {
@@ -668,10 +684,15 @@ static int check_slice_limits(const moe_shape* s) {
 
 template <typename T, int BM, int BN, int BK>
 static void ffn_fwd(const moe_shape* s, const void* xd, const int32_t* cnt, const void* W1,
-                    const void* W2, void* h, void* a, void* yd, hipStream_t st) {
+                    const void* W2, void* h, void* a, void* yd, float drop_p, uint64_t seed, hipStream_t st) {
     const int E = s->E, C = s->capacity, d = s->d_model, f = s->d_ff;
     GemmArgs p = {};
     p.expert_count = cnt; p.var_k = 0;
+    if (drop_p > 0.0f) {
+        p.drop_thr = (uint32_t)floor((double)drop_p * 4294967296.0);
+        p.drop_scale = (float)(1.0 / (1.0 - (double)drop_p));
+        p.seed = seed;
+    }
     // z = xd W1 (not stored);  h = act(z), a = act'(z)
     p.A = xd; p.lda = d; p.strideA = (long long)C * d;
     p.B = W1; p.ldb = f; p.strideB = (long long)d * f;
@@ -688,6 +709,7 @@ static void ffn_fwd(const moe_shape* s, const void* xd, const int32_t* cnt, cons
     p.B = W2; p.ldb = d; p.strideB = (long long)f * d;
     p.out0 = yd; p.out1 = nullptr; p.ldo = d; p.strideO = (long long)C * d;
     p.M = C; p.N = d; p.K = f;
+    p.drop_thr = 0;
     launch_gemm<T, BM, BN, BK, true, false, EPI_STORE>(p, E, st);
 }
 
@@ -726,19 +748,35 @@ static void ffn_bwd(const moe_shape* s, const void* dyd, const void* xd, const v
     launch_gemm<T, BM, BN, BK, false, false, EPI_F32>(p, E, st);
 }
 
-extern "C" int moe_expert_ffn_fwd(const moe_shape* shape, const void* xd,
-                                  const int32_t* expert_count, const void* W1, const void* W2,
-                                  void* h_saved, void* dact_saved, void* yd, void* stream) {
+static int ffn_fwd_impl(const moe_shape* shape, const void* xd, const int32_t* expert_count,
+                        const void* W1, const void* W2, float drop_p, uint64_t seed, void* h_saved,
+                        void* dact_saved, void* yd, void* stream) {
     int rc = check_shape(shape);
     if (rc) return rc;
     if ((rc = check_slice_limits(shape))) return rc;
     if (!xd || !expert_count || !W1 || !W2 || !h_saved || !yd) return MOE_ERR_NULL;   // dact_saved may be NULL
+    if (!(drop_p >= 0.0f && drop_p < 1.0f)) return MOE_ERR_SHAPE;
+    if (drop_p > 0.0f && !dact_saved) return MOE_ERR_NULL;      // dropout is a training feature
+    if (drop_p > 0.0f && floor((double)drop_p * 4294967296.0) < 1.0) drop_p = 0.0f;   // below one part in 2^32
     hipStream_t st = (hipStream_t)stream;
     if (shape->dtype == MOE_BF16)
-        ffn_fwd<bf16_t, MOE_GEMM_BM, MOE_GEMM_BN, MOE_GEMM_BK>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, st);
+        ffn_fwd<bf16_t, MOE_GEMM_BM, MOE_GEMM_BN, MOE_GEMM_BK>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, drop_p, seed, st);
     else
-        ffn_fwd<float, 128, 128, 16>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, st);
+        ffn_fwd<float, 128, 128, 16>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, drop_p, seed, st);
     return launch_status();
+}
+
+extern "C" int moe_expert_ffn_fwd(const moe_shape* shape, const void* xd,
+                                  const int32_t* expert_count, const void* W1, const void* W2,
+                                  void* h_saved, void* dact_saved, void* yd, void* stream) {
+    return ffn_fwd_impl(shape, xd, expert_count, W1, W2, 0.0f, 0, h_saved, dact_saved, yd, stream);
+}
+
+extern "C" int moe_expert_ffn_fwd_dropout(const moe_shape* shape, const void* xd,
+                                          const int32_t* expert_count, const void* W1, const void* W2,
+                                          float drop_p, uint64_t seed, void* h_saved, void* dact_saved,
+                                          void* yd, void* stream) {
+    return ffn_fwd_impl(shape, xd, expert_count, W1, W2, drop_p, seed, h_saved, dact_saved, yd, stream);
 }
 
 extern "C" int moe_expert_ffn_bwd(const moe_shape* shape, const void* dyd, const void* xd,

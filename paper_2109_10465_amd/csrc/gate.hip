@@ -35,7 +35,7 @@ __device__ __forceinline__ void load8<float>(__amdgpu_buffer_rsrc_t rs, uint32_t
 template <typename T, int NB>
 __global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
     int Tn, int d, int E, const T* __restrict__ x, const float* __restrict__ Wg,
-    const float* __restrict__ bias, float* __restrict__ logits) {
+    const float* __restrict__ bias, float* __restrict__ logits, float jitter_eps, uint64_t seed) {
     constexpr int GRP = NB <= 2 ? 8 : 4;   // 16-deep blocks whose loads are in flight together
     __shared__ float red[GLM_KSPLIT][32][33];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -59,6 +59,11 @@ __global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
             const int k = (b0 + u) * 16 + 8 * h;
             const bool ok = b0 + u < b_hi && k < d;     // rows beyond T fall outside rs_x
             load8<T>(rs_x, ok ? (uint32_t)((r * d + k) * sizeof(T)) : BUF_OOB, a[u]);
+        }
+        if (jitter_eps != 0.0f) {   // the gate sees x * noise (uniform branch)
+#pragma unroll
+            for (int u = 0; u < GRP; ++u)
+                jitter_scale<8>(a[u], (size_t)(t0 + r) * d + (b0 + u) * 16 + 8 * h, jitter_eps, seed);
         }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -99,21 +104,33 @@ __global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
 
 template <typename T>
 static void launch_gate_logits(const moe_shape* s, const void* x, const float* Wg, const float* bias,
-                               float* logits, hipStream_t st) {
+                               float* logits, float eps, uint64_t seed, hipStream_t st) {
     const int grid = ceil_div(s->T, 32);
-#define GLM(NB) gate_logits_kernel<T, NB><<<grid, 64 * GLM_KSPLIT, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits)
+#define GLM(NB) gate_logits_kernel<T, NB><<<grid, 64 * GLM_KSPLIT, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits, eps, seed)
     if (s->E <= 32) GLM(1); else if (s->E <= 64) GLM(2); else if (s->E <= 128) GLM(4); else GLM(8);
 #undef GLM
 }
 
-extern "C" int moe_gate_logits(const moe_shape* shape, const void* x, const float* Wg,
-                               const float* bias_or_null, float* logits, void* stream) {
+static int gate_logits_impl(const moe_shape* shape, const void* x, const float* Wg,
+                            const float* bias_or_null, float eps, uint64_t seed, float* logits, void* stream) {
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!x || !Wg || !logits) return MOE_ERR_NULL;
-    if (shape->dtype == MOE_BF16) launch_gate_logits<bf16_t>(shape, x, Wg, bias_or_null, logits, (hipStream_t)stream);
-    else launch_gate_logits<float>(shape, x, Wg, bias_or_null, logits, (hipStream_t)stream);
+    if (!(eps >= 0.0f && eps < 1.0f)) return MOE_ERR_SHAPE;
+    if (shape->dtype == MOE_BF16) launch_gate_logits<bf16_t>(shape, x, Wg, bias_or_null, logits, eps, seed, (hipStream_t)stream);
+    else launch_gate_logits<float>(shape, x, Wg, bias_or_null, logits, eps, seed, (hipStream_t)stream);
     return launch_status();
+}
+
+extern "C" int moe_gate_logits(const moe_shape* shape, const void* x, const float* Wg,
+                               const float* bias_or_null, float* logits, void* stream) {
+    return gate_logits_impl(shape, x, Wg, bias_or_null, 0.0f, 0, logits, stream);
+}
+
+extern "C" int moe_gate_logits_jitter(const moe_shape* shape, const void* x, const float* Wg,
+                                      const float* bias_or_null, float jitter_eps, uint64_t seed,
+                                      float* logits, void* stream) {
+    return gate_logits_impl(shape, x, Wg, bias_or_null, jitter_eps, seed, logits, stream);
 }
 
 // ---------------------------------------------------------------------------
@@ -194,7 +211,7 @@ size_t gate_logits_bwd_ws_bytes(const moe_shape* s) {
 template <typename T>
 __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
     int Tn, int d, int E, int tok_per_chunk, const T* __restrict__ x,
-    const float* __restrict__ dlogits, float* __restrict__ partial) {
+    const float* __restrict__ dlogits, float* __restrict__ partial, float jitter_eps, uint64_t seed) {
     extern __shared__ __align__(16) float gw_red[];      // [wave][256 columns][32 experts]
     constexpr int GRP = sizeof(T) == 2 ? 8 : 4;          // token pairs whose loads are in flight together
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -225,7 +242,12 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
             fb[u] = buf_load_f32(rs_d, ok && e_ok ? (uint32_t)(((tok - tbeg) * E + e0 + r) * 4) : BUF_OOB);
         }
     };
-    auto multiply = [&](const float (&fa)[GRP][8], const float (&fb)[GRP]) {
+    auto multiply = [&](int t, float (&fa)[GRP][8], const float (&fb)[GRP]) {
+        if (jitter_eps != 0.0f) {   // dWg = (x * noise)^T dlogits (uniform branch)
+#pragma unroll
+            for (int u = 0; u < GRP; ++u)
+                jitter_scale<8>(fa[u], (size_t)(t + 2 * u + h) * d + col, jitter_eps, seed);
+        }
 #pragma unroll
         for (int u = 0; u < GRP; ++u)
 #pragma unroll
@@ -234,9 +256,9 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
     fetch(w_lo, a[0], b[0]);
     for (int t = w_lo; t < w_hi; t += 4 * GRP) {
         fetch(t + 2 * GRP, a[1], b[1]);      // beyond w_hi: every lane reads zeros, harmless
-        multiply(a[0], b[0]);
+        multiply(t, a[0], b[0]);
         fetch(t + 4 * GRP, a[0], b[0]);
-        multiply(a[1], b[1]);
+        multiply(t + 2 * GRP, a[1], b[1]);
     }
     // accumulator v of tile c, lane l: column i0 + 8*(8*(v/4) + 4*(l/32) + v%4) + c, expert e0 + l%32
 #pragma unroll
@@ -307,7 +329,7 @@ template <typename T, int EB, bool VEC>   // EB = 32-expert blocks (E <= 32*EB);
 __global__ __launch_bounds__(512) void gate_dx_kernel(int Tn, int d, int E,
                                                       const float* __restrict__ dlogits,
                                                       const float* __restrict__ Wg,
-                                                      T* __restrict__ dx) {
+                                                      T* __restrict__ dx, float jitter_eps, uint64_t seed) {
     constexpr bool HOIST = EB <= 2;      // dlogits fragments stay in registers across column blocks
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, h = lane >> 5;
@@ -346,10 +368,15 @@ __global__ __launch_bounds__(512) void gate_dx_kernel(int Tn, int d, int E,
             for (int s_ = 0; s_ < 16; ++s_)
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(afr[s_], bfr[HOIST ? eb : 0][s_], acc, 0, 0, 0);
         }
+        float inc[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) inc[v] = acc[v];
+        if (jitter_eps != 0.0f)     // the gate saw x * noise: d/dx carries the factor (uniform branch)
+            jitter_scale<16>(inc, (size_t)(t0 + r) * d + c0, jitter_eps, seed);
 #pragma unroll
         for (int q = 0; q < NCH; ++q) {   // stores beyond T or d are dropped by the range check
 #pragma unroll
-            for (int j = 0; j < CN; ++j) cur[q][j] += acc[q * CN + j];
+            for (int j = 0; j < CN; ++j) cur[q][j] += inc[q * CN + j];
             BufChunk<T>::store(rs_dx, c0 + q * CN < d ? (uint32_t)((r * d + c0 + q * CN) * sizeof(T)) : BUF_OOB, cur[q]);
         }
     }
@@ -358,7 +385,7 @@ __global__ __launch_bounds__(512) void gate_dx_kernel(int Tn, int d, int E,
 template <typename T>
 static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const float* Wg,
                                    const float* dlogits, float* dWg, void* dx, float* partial,
-                                   hipStream_t st) {
+                                   float eps, uint64_t seed, hipStream_t st) {
     const int tpc = gw_chunk_tokens(s);
     const int nch_used = ceil_div(s->T, tpc);
     dim3 grid(ceil_div(s->d_model, GW_COLS), nch_used, ceil_div(s->E, 32));
@@ -367,12 +394,12 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
         (const void*)gate_dwg_partial_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)red_bytes);
     (void)attr;
     gate_dwg_partial_kernel<T><<<grid, 64 * GW_WAVES, red_bytes, st>>>(s->T, s->d_model, s->E, tpc, (const T*)x,
-                                                                      dlogits, partial);
+                                                                      dlogits, partial, eps, seed);
     const int n = s->d_model * s->E;
     gate_dwg_reduce_kernel<<<ceil_div(n, 256), 256, 0, st>>>(n, nch_used, partial, dWg);
     if (dx) {
         const int grid_dx = ceil_div(s->T, 32);
-#define GDX(EB, VEC) gate_dx_kernel<T, EB, VEC><<<grid_dx, 512, 0, st>>>(s->T, s->d_model, s->E, dlogits, Wg, (T*)dx)
+#define GDX(EB, VEC) gate_dx_kernel<T, EB, VEC><<<grid_dx, 512, 0, st>>>(s->T, s->d_model, s->E, dlogits, Wg, (T*)dx, eps, seed)
 #define GDXE(VEC) do { if (s->E <= 32) GDX(1, VEC); else if (s->E <= 64) GDX(2, VEC); \
                        else if (s->E <= 128) GDX(4, VEC); else GDX(8, VEC); } while (0)
         if (s->E % 4 == 0) GDXE(true); else GDXE(false);
@@ -381,16 +408,30 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
     }
 }
 
-extern "C" int moe_gate_logits_bwd(const moe_shape* shape, const void* x, const float* Wg,
-                                   const float* dlogits, float* dWg, void* dx_accum, void* ws,
-                                   size_t ws_bytes, void* stream) {
+static int gate_logits_bwd_impl(const moe_shape* shape, const void* x, const float* Wg, const float* dlogits,
+                                float eps, uint64_t seed, float* dWg, void* dx_accum, void* ws,
+                                size_t ws_bytes, void* stream) {
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!x || !Wg || !dlogits || !dWg) return MOE_ERR_NULL;
+    if (!(eps >= 0.0f && eps < 1.0f)) return MOE_ERR_SHAPE;
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < gate_logits_bwd_ws_bytes(shape)) return MOE_ERR_WORKSPACE;
     if (shape->dtype == MOE_BF16)
-        launch_gate_logits_bwd<bf16_t>(shape, x, Wg, dlogits, dWg, dx_accum, (float*)ws, (hipStream_t)stream);
+        launch_gate_logits_bwd<bf16_t>(shape, x, Wg, dlogits, dWg, dx_accum, (float*)ws, eps, seed, (hipStream_t)stream);
     else
-        launch_gate_logits_bwd<float>(shape, x, Wg, dlogits, dWg, dx_accum, (float*)ws, (hipStream_t)stream);
+        launch_gate_logits_bwd<float>(shape, x, Wg, dlogits, dWg, dx_accum, (float*)ws, eps, seed, (hipStream_t)stream);
     return launch_status();
+}
+
+extern "C" int moe_gate_logits_bwd(const moe_shape* shape, const void* x, const float* Wg,
+                                   const float* dlogits, float* dWg, void* dx_accum, void* ws,
+                                   size_t ws_bytes, void* stream) {
+    return gate_logits_bwd_impl(shape, x, Wg, dlogits, 0.0f, 0, dWg, dx_accum, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_gate_logits_bwd_jitter(const moe_shape* shape, const void* x, const float* Wg,
+                                          const float* dlogits, float jitter_eps, uint64_t seed,
+                                          float* dWg, void* dx_accum, void* ws, size_t ws_bytes,
+                                          void* stream) {
+    return gate_logits_bwd_impl(shape, x, Wg, dlogits, jitter_eps, seed, dWg, dx_accum, ws, ws_bytes, stream);
 }

@@ -152,6 +152,42 @@ template <> struct Vec4buf<bf16_t> {
     }
 };
 
+// ---- seeded noise: Philox4x32 with 10 rounds (Salmon et al., SC 2011) --------------
+// Element i of a tensor uses word i % 4 of the block with counter
+// (i/4 low word, i/4 high word, stream, 0) and key (seed low word, seed high word).
+#define MOE_STREAM_JITTER 1u
+#define MOE_STREAM_DROPOUT 2u
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0; c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+// words of the 4 consecutive elements that start at element index `first` (a multiple of 4)
+__device__ __forceinline__ void noise_words(size_t first, uint32_t stream, uint64_t seed, uint32_t (&w)[4]) {
+    const size_t blk = first >> 2;
+    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), stream, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w);
+}
+// Gate jitter (Sec. 5.1): v[j] *= 1 + eps (2 u_j - 1), u_j = word_j / 2^32, for the N
+// consecutive elements (N = 4, 8 or 16) starting at element index `first`
+template <int N>
+__device__ __forceinline__ void jitter_scale(float (&v)[N], size_t first, float eps, uint64_t seed) {
+    const float a = eps * 4.656612873077393e-10f, b = 1.0f - eps;    // 2 eps / 2^32
+#pragma unroll
+    for (int q = 0; q < N / 4; ++q) {
+        uint32_t w[4];
+        noise_words(first + 4 * q, MOE_STREAM_JITTER, seed, w);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[4 * q + j] *= fmaf(a, (float)w[j], b);
+    }
+}
+
 // ---- wave64 reductions (butterfly: every lane ends with the same bits) ------
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

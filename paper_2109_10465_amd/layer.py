@@ -13,7 +13,7 @@ _TORCH_DT = {B.F32: torch.float32, B.BF16: torch.bfloat16}
 
 class MoELayer:
     def __init__(self, T, d_model, d_ff, E, k, capacity, dtype, act, device="cuda:0", aux_coef=0.0,
-                 forward_only=False, groups=1):
+                 forward_only=False, groups=1, jitter_eps=0.0, drop_p=0.0):
         if not torch.cuda.is_available():
             raise B.MoeError("MoELayer needs a GPU; there is no CPU fallback")
         B.lib()
@@ -21,6 +21,9 @@ class MoELayer:
         self.T, self.d, self.f, self.E, self.k, self.C = T, d_model, d_ff, E, k, capacity
         self.device = torch.device(device)
         self.aux_coef = float(aux_coef)     # weight of the balancing loss in the objective (0 = off)
+        self.jitter_eps = float(jitter_eps)  # gate jitter (training); the seed is given per step
+        self.drop_p = float(drop_p)          # expert dropout on the hidden activation (training)
+        self.seed = 0
         self.groups = int(groups)           # > 1: token selection inside groups of T/groups consecutive tokens
         self.forward_only = bool(forward_only)   # evaluation: no saved derivative, no backward buffers
         adt = _TORCH_DT[dtype]
@@ -63,13 +66,14 @@ class MoELayer:
         self.dWg = buf((d_model, E), f32)
         self.dx = buf((T, d_model), adt)
 
-    def forward(self, x, Wg, bias, W1, W2, rts_keys, logits=None):
+    def forward(self, x, Wg, bias, W1, W2, rts_keys, logits=None, seed=0):
         """logits: optional precomputed [T,E] fp32 gate logits; the projection call is
         then skipped and routing runs on exactly these values."""
         s = self.shape
         self._saved = (x, Wg, W1, W2)
+        self.seed = int(seed)     # of this step's jitter and dropout draws
         if logits is None:
-            B.moe_gate_logits(s, x, Wg, bias, self.logits)
+            B.moe_gate_logits_jitter(s, x, Wg, bias, self.jitter_eps, self.seed, self.logits)
         else:
             self.logits.copy_(logits)
         if self.groups > 1:
@@ -85,7 +89,11 @@ class MoELayer:
             B.moe_aux_loss(s, self.probs, self.expert_idx, self.first_frac, self.mean_prob, self.aux_loss,
                            self.ws)
         B.moe_dispatch(s, x, self.slot_src, self.expert_count, self.xd)
-        B.moe_expert_ffn_fwd(s, self.xd, self.expert_count, W1, W2, self.h, self.dact, self.yd)
+        if self.drop_p > 0.0:
+            B.moe_expert_ffn_fwd_dropout(s, self.xd, self.expert_count, W1, W2, self.drop_p, self.seed, self.h,
+                                         self.dact, self.yd)
+        else:
+            B.moe_expert_ffn_fwd(s, self.xd, self.expert_count, W1, W2, self.h, self.dact, self.yd)
         B.moe_combine_fwd(s, self.yd, self.expert_idx, self.slot, self.gate_w, self.y)
         return self.y
 
@@ -105,9 +113,10 @@ class MoELayer:
                                self.aux_coef, self.dlogits)
         else:
             B.moe_gate_bwd(s, self.dgate_w, self.probs, self.expert_idx, self.slot, self.dlogits)
-        B.moe_gate_logits_bwd(s, x, Wg, self.dlogits, self.dWg, self.dx, self.ws)
+        B.moe_gate_logits_bwd_jitter(s, x, Wg, self.dlogits, self.jitter_eps, self.seed, self.dWg, self.dx,
+                                     self.ws)
         return self.dx, self.dWg, self.dW1, self.dW2
 
-    def step(self, x, Wg, bias, W1, W2, rts_keys, dy, logits=None):
-        self.forward(x, Wg, bias, W1, W2, rts_keys, logits)
+    def step(self, x, Wg, bias, W1, W2, rts_keys, dy, logits=None, seed=0):
+        self.forward(x, Wg, bias, W1, W2, rts_keys, logits, seed)
         return self.backward(dy)

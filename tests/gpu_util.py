@@ -32,11 +32,12 @@ def rel_l2(got, want):
     return num / den if den > 0 else num
 
 
-def run_layer(w, d, use_keys=True, logits=None, aux_coef=0.0, groups=1):
+def run_layer(w, d, use_keys=True, logits=None, aux_coef=0.0, groups=1, jitter_eps=0.0, drop_p=0.0, seed=0):
     """One forward+backward of workload w on the GPU; returns (layer, dict of
     host arrays) with the same names the oracle uses.  logits (fp32 numpy, made
     by the oracle) replaces the GPU's gate projection as the router's input."""
-    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act, aux_coef=aux_coef, groups=groups)
+    layer = MoELayer(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act, aux_coef=aux_coef, groups=groups,
+                     jitter_eps=jitter_eps, drop_p=drop_p)
     x, dy = to_dev(d["x"], w.dtype), to_dev(d["dy"], w.dtype)
     W1, W2 = to_dev(d["W1"], w.dtype), to_dev(d["W2"], w.dtype)
     Wg = to_dev(d["Wg"], I.F32)
@@ -44,7 +45,7 @@ def run_layer(w, d, use_keys=True, logits=None, aux_coef=0.0, groups=1):
     keys = to_dev(d["rts_keys"], I.F32) if use_keys else None
     print(f"[gpu] {w.name}: T={w.T} d={w.d_model} f={w.d_ff} E={w.E} k={w.k} C={w.capacity} "
           f"dtype={w.dtype} keys={use_keys} logits={'gpu' if logits is None else 'given'}", flush=True)
-    layer.step(x, Wg, bias, W1, W2, keys, dy, None if logits is None else to_dev(logits, I.F32))
+    layer.step(x, Wg, bias, W1, W2, keys, dy, None if logits is None else to_dev(logits, I.F32), seed)
     torch.cuda.synchronize()
     names = ["logits", "probs", "expert_idx", "gate_w", "slot", "expert_count", "expert_demand",
              "slot_src", "xd", "h", "dact", "yd", "y", "dyd", "dgate_w", "dxd", "dW1", "dW2",
@@ -55,10 +56,13 @@ def run_layer(w, d, use_keys=True, logits=None, aux_coef=0.0, groups=1):
     return layer, out
 
 
-def oracle_logits(d):
+def oracle_logits(d, jitter_eps=0.0, seed=0):
     """The oracle's gate logits in fp64 and rounded to fp32, the precision in
     which both sides take the top-k decision."""
-    ref64 = O.gate_logits(d["x"], d["Wg"], d["bias"])
+    xg = np.asarray(d["x"], np.float64)
+    if jitter_eps != 0.0:
+        xg = xg * O.jitter_noise(xg.shape[0], xg.shape[1], jitter_eps, seed)
+    ref64 = O.gate_logits(xg, d["Wg"], d["bias"])
     return ref64, ref64.astype(np.float32)
 
 
@@ -103,7 +107,7 @@ def row_mask(count, C):
     return np.arange(C)[None, :] < np.asarray(count)[:, None]
 
 
-def compare_full(w, d, got, ref, aux=False):
+def compare_full(w, d, got, ref, aux=False, scale=None):
     """Element-by-element comparison of every output of one GPU run with the
     oracle's: integers bit-exact, floats by rel-L2.  Returns the errors."""
     tol = TOL[w.dtype]
@@ -115,6 +119,8 @@ def compare_full(w, d, got, ref, aux=False):
         assert errs[n] <= 1e-5, (n, errs[n])
     m = row_mask(ref["expert_count"], w.capacity)
     dact = O.act_grad(ref["Z"], w.act)          # the derivative the forward saves
+    if scale is not None:                       # expert dropout folds its factor into it
+        dact = dact * scale
     pairs = [("xd", ref["Xd"]), ("h", ref["H"]), ("dact", dact), ("yd", ref["Yd"]), ("dyd", ref["dYd"]),
              ("dxd", ref["dXd"])]
     for g, r in pairs:
