@@ -32,7 +32,7 @@ __device__ __forceinline__ void load8<float>(__amdgpu_buffer_rsrc_t rs, uint32_t
     for (int i = 0; i < 4; ++i) { v[i] = lo[i]; v[4 + i] = hi[i]; }
 }
 
-template <typename T, int NB>
+template <typename T, int NB, bool JIT>   // JIT: gate jitter on (a separate instance keeps the plain one lean)
 __global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
     int Tn, int d, int E, const T* __restrict__ x, const float* __restrict__ Wg,
     const float* __restrict__ bias, float* __restrict__ logits, float jitter_eps, uint64_t seed) {
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
             const bool ok = b0 + u < b_hi && k < d;     // rows beyond T fall outside rs_x
             load8<T>(rs_x, ok ? (uint32_t)((r * d + k) * sizeof(T)) : BUF_OOB, a[u]);
         }
-        if (jitter_eps != 0.0f) {   // the gate sees x * noise (uniform branch)
+        if constexpr (JIT) {   // the gate sees x * noise
 #pragma unroll
             for (int u = 0; u < GRP; ++u)
                 jitter_scale<8>(a[u], (size_t)(t0 + r) * d + (b0 + u) * 16 + 8 * h, jitter_eps, seed);
@@ -106,8 +106,11 @@ template <typename T>
 static void launch_gate_logits(const moe_shape* s, const void* x, const float* Wg, const float* bias,
                                float* logits, float eps, uint64_t seed, hipStream_t st) {
     const int grid = ceil_div(s->T, 32);
-#define GLM(NB) gate_logits_kernel<T, NB><<<grid, 64 * GLM_KSPLIT, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits, eps, seed)
-    if (s->E <= 32) GLM(1); else if (s->E <= 64) GLM(2); else if (s->E <= 128) GLM(4); else GLM(8);
+#define GLM(NB, JIT) gate_logits_kernel<T, NB, JIT><<<grid, 64 * GLM_KSPLIT, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits, eps, seed)
+#define GLME(JIT) do { if (s->E <= 32) GLM(1, JIT); else if (s->E <= 64) GLM(2, JIT); \
+                       else if (s->E <= 128) GLM(4, JIT); else GLM(8, JIT); } while (0)
+    if (eps != 0.0f) GLME(true); else GLME(false);
+#undef GLME
 #undef GLM
 }
 
@@ -208,12 +211,12 @@ size_t gate_logits_bwd_ws_bytes(const moe_shape* s) {
     return align_up((size_t)ceil_div(s->T, gw_chunk_tokens(s)) * s->d_model * s->E * 4, 256);
 }
 
-template <typename T>
+template <typename T, bool JIT>
 __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
     int Tn, int d, int E, int tok_per_chunk, const T* __restrict__ x,
     const float* __restrict__ dlogits, float* __restrict__ partial, float jitter_eps, uint64_t seed) {
     extern __shared__ __align__(16) float gw_red[];      // [wave][256 columns][32 experts]
-    constexpr int GRP = sizeof(T) == 2 ? 8 : 4;          // token pairs whose loads are in flight together
+    constexpr int GRP = 4;                               // token pairs whose loads are in flight together (x2 buffers)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, h = lane >> 5;
     const int i0 = blockIdx.x * GW_COLS, e0 = blockIdx.z * 32;
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
         }
     };
     auto multiply = [&](int t, float (&fa)[GRP][8], const float (&fb)[GRP]) {
-        if (jitter_eps != 0.0f) {   // dWg = (x * noise)^T dlogits (uniform branch)
+        if constexpr (JIT) {   // dWg = (x * noise)^T dlogits
 #pragma unroll
             for (int u = 0; u < GRP; ++u)
                 jitter_scale<8>(fa[u], (size_t)(t + 2 * u + h) * d + col, jitter_eps, seed);
@@ -390,11 +393,17 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
     const int nch_used = ceil_div(s->T, tpc);
     dim3 grid(ceil_div(s->d_model, GW_COLS), nch_used, ceil_div(s->E, 32));
     constexpr size_t red_bytes = (size_t)GW_WAVES * GW_COLS * 32 * sizeof(float);   // 128 KB: opt in beyond 64 KB
-    static const hipError_t attr = hipFuncSetAttribute(
-        (const void*)gate_dwg_partial_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)red_bytes);
-    (void)attr;
-    gate_dwg_partial_kernel<T><<<grid, 64 * GW_WAVES, red_bytes, st>>>(s->T, s->d_model, s->E, tpc, (const T*)x,
-                                                                      dlogits, partial, eps, seed);
+    static const hipError_t attr0 = hipFuncSetAttribute(
+        (const void*)gate_dwg_partial_kernel<T, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)red_bytes);
+    static const hipError_t attr1 = hipFuncSetAttribute(
+        (const void*)gate_dwg_partial_kernel<T, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)red_bytes);
+    (void)attr0; (void)attr1;
+    if (eps != 0.0f)
+        gate_dwg_partial_kernel<T, true><<<grid, 64 * GW_WAVES, red_bytes, st>>>(s->T, s->d_model, s->E, tpc,
+                                                                              (const T*)x, dlogits, partial, eps, seed);
+    else
+        gate_dwg_partial_kernel<T, false><<<grid, 64 * GW_WAVES, red_bytes, st>>>(s->T, s->d_model, s->E, tpc,
+                                                                               (const T*)x, dlogits, partial, eps, seed);
     const int n = s->d_model * s->E;
     gate_dwg_reduce_kernel<<<ceil_div(n, 256), 256, 0, st>>>(n, nch_used, partial, dWg);
     if (dx) {
