@@ -186,6 +186,15 @@ template <typename T, int BR, int BK, bool KC, int NT> struct Tile {
             load_to_lds(ds, off, __builtin_amdgcn_readfirstlane(wave_base + i * NT * 16));
         }
     }
+    // The i-th of this thread's loads alone (to spread a slab's requests between MFMAs).
+    __device__ static __forceinline__ void issue_one(const Plan& pl, u32x4_t ds, int ld, int k0, int k_lim,
+                                                     uint32_t lds_base, int i) {
+        const uint32_t kstep = (uint32_t)(KC ? k0 : k0 * ld) * (uint32_t)sizeof(T);
+        const uint32_t wave_base = lds_base + (threadIdx.x >> 6) * 1024;
+        uint32_t off = pl.voff[i] + kstep;
+        if (KC) off = pl.kcol[i] + k0 < k_lim ? off : OOB_OFFSET;
+        load_to_lds(ds, off, __builtin_amdgcn_readfirstlane(wave_base + i * NT * 16));
+    }
     // LDS -> MFMA operand for the 32 tile rows rbase..rbase+31 (this lane: row
     // rbase + lane%32), reduction step ks; lane group g = lane/32 holds the
     // reduction entries ks*KSTEP + FE*g .. + FE-1.
@@ -454,25 +463,38 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
     // requests the next slab of the stream into ring stage `st`; past the end of
     // the stream it requests out-of-range loads (zeros) so that every slab counts
     // the same number of loads in vmcnt
-    auto produce = [&](int st) {
+    // The request of a slab is split in two so that, inside the main loop, its
+    // loads can be issued one at a time between MFMAs (a burst of all of them fills
+    // the address FIFO of the memory pipe and stalls the wave's instruction issue).
+    int pk0 = 0, pkl = 0;
+    uint32_t plds = 0;
+    u32x4_t pua = {0, 0, 0, 0}, pub = {0, 0, 0, 0};
+    auto produce_prepare = [&](int st) {
         while (p_more && p_kt >= p_nk) {
             p_more = pw.next(p);
             if (p_more) producer_setup();
         }
-        const int k0 = p_more ? p_kt * BK : 0;
-        const int kl = p_more ? pw.k_lim : 0;     // k_lim 0: every guard fails, nothing is read
+        pk0 = p_more ? p_kt * BK : 0;
+        pkl = p_more ? pw.k_lim : 0;              // k_lim 0: every guard fails, nothing is read
         if (!p_more) { dsA[2] = 0; dsB[2] = 0; }  // empty range: every load returns zeros
         // the descriptors are wave-uniform by construction; say so to the compiler
         // (they must sit in scalar registers for the load instruction)
-        u32x4_t ua, ub;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            ua[i] = __builtin_amdgcn_readfirstlane(dsA[i]);
-            ub[i] = __builtin_amdgcn_readfirstlane(dsB[i]);
+            pua[i] = __builtin_amdgcn_readfirstlane(dsA[i]);
+            pub[i] = __builtin_amdgcn_readfirstlane(dsB[i]);
         }
-        TA::issue(planA, ua, p.lda, k0, kl, lds0 + st * SM::STAGE);
-        TB::issue(planB, ub, p.ldb, k0, kl, lds0 + st * SM::STAGE + TA::BYTES);
+        plds = lds0 + st * SM::STAGE;
         ++p_kt;
+    };
+    auto produce_issue = [&](int i) {   // load i of the prepared slab (i < SM::LOADS; A's loads come first)
+        if (i < TA::PER_THREAD) TA::issue_one(planA, pua, p.lda, pk0, pkl, plds, i);
+        else TB::issue_one(planB, pub, p.ldb, pk0, pkl, plds + TA::BYTES, i - TA::PER_THREAD);
+    };
+    auto produce = [&](int st) {
+        produce_prepare(st);
+#pragma unroll
+        for (int i = 0; i < SM::LOADS; ++i) produce_issue(i);
     };
 
 #ifdef MOE_GEMM_CLOCKDBG
@@ -554,12 +576,23 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                     wait_vmcnt_lgkm0<(NS - 2) * SM::LOADS>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
-                    produce(stage);
+                    produce_prepare(stage);
                     const unsigned char* a_n = smem_raw + next * SM::STAGE;
+                    // hand-laid schedule of the last step: per MFMA one slab request and one
+                    // fragment read of the next slab
+                    constexpr int NMMA = TM * TN, LPM = (SM::LOADS + NMMA - 1) / NMMA;
 #pragma unroll
-                    for (int i = 0; i < TM; ++i) fa[n][i] = TA::frag(a_n, wm * (BM / 2) + i * 32, 0, lane);
+                    for (int q = 0; q < NMMA; ++q) {
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) fb[n][j] = TB::frag(a_n + TA::BYTES, wn * WCOLS + j * 32, 0, lane);
+                        for (int u = 0; u < LPM; ++u)
+                            if (q * LPM + u < SM::LOADS) produce_issue(q * LPM + u);
+                        if (q < TM) fa[n][q] = TA::frag(a_n, wm * (BM / 2) + q * 32, 0, lane);
+                        else if (q < TM + TN) fb[n][q - TM] = TB::frag(a_n + TA::BYTES, wn * WCOLS + (q - TM) * 32, 0, lane);
+                        acc[q / TN][q % TN] = Mma<T>::mma(fa[c][q / TN], fb[c][q % TN], acc[q / TN][q % TN]);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    static_assert(TM + TN <= NMMA, "one fragment read per MFMA slot");
+                    continue;
                 }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
