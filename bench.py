@@ -138,23 +138,26 @@ def main():
 
     # timed region: exactly K steps; HIP events (torch's current stream is the
     # stream the kernels are launched on) bracket the expert-GEMM calls
-    n_gemm_calls = sum(1 for n, _ in calls if n in gemm_calls)
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2 * n_gemm_calls)] for _ in range(args.steps)]
+    # and, for the HBM-bound steps the metric also names, the route / dispatch / combine calls
+    hbm_calls = ("gate_route", "dispatch", "combine_fwd", "combine_bwd", "dispatch_bwd")
+    timed = [n for n, _ in calls if n in gemm_calls or n in hbm_calls]
+    ev = [{n: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for n in timed}
+          for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        e = iter(ev[i])
         for name, fn in calls:
-            if name in gemm_calls:
-                next(e).record()
+            if name in ev[i]:
+                ev[i][name][0].record()
                 fn()
-                next(e).record()
+                ev[i][name][1].record()
             else:
                 fn()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    gemm_ms = sum(sum(e[2 * i].elapsed_time(e[2 * i + 1]) for i in range(n_gemm_calls)) for e in ev) / args.steps
+    call_ms = {n: sum(e[n][0].elapsed_time(e[n][1]) for e in ev) / args.steps for n in timed}
+    gemm_ms = sum(v for n, v in call_ms.items() if n in gemm_calls)
 
     M = int(L.expert_count.sum().item())                      # kept assignments actually routed
     n_gemm = 2 if args.forward_only else 6
@@ -173,6 +176,25 @@ def main():
                 "flops_per_launch": flops / n_gemm, "avg_launch_ms": gemm_ms / n_gemm,
                 "kept_assignments": M}
 
+    # algorithmic HBM bytes per call (each tensor once; gathered rows counted per use)
+    sb = 2 if w.dtype == I.BF16 else 4
+    Tn, dm, E, k, C = w.T, w.d_model, w.E, w.k, w.capacity
+    kept_tok = int((L.slot >= 0).any(dim=1).sum().item())
+    alg = {
+        "gate_logits": Tn * dm * sb + dm * E * 4 + Tn * E * 4,
+        "gate_route": Tn * E * 4 * 2 + 12 * Tn * k + 4 * Tn + 4 * Tn * k + 4 * E * C + 8 * E,
+        "dispatch": kept_tok * dm * sb + 4 * E * C + M * dm * sb,
+        "combine_fwd": M * dm * sb + 12 * Tn * k + Tn * dm * sb,
+        "combine_bwd": Tn * dm * sb + M * dm * sb + M * dm * sb + 4 * Tn * k,
+        "dispatch_bwd": M * dm * sb + 8 * Tn * k + Tn * dm * sb,
+        "gate_bwd": Tn * E * 4 * 2 + 16 * Tn * k,
+        "aux_loss": Tn * E * 4 + 4 * Tn * k,
+        "gate_logits_bwd": 2 * Tn * dm * sb + Tn * E * 4 + Tn * dm * sb + dm * E * 8,
+    }
+    hbm = {n: {"us": call_ms[n] * 1e3, "GBps": alg[n] / (call_ms[n] * 1e-3) / 1e9,
+               "frac_of_8TBps": alg[n] / (call_ms[n] * 1e-3) / PEAK_HBM}
+           for n in hbm_calls if n in call_ms}
+
     breakdown = None
     if args.breakdown:
         n = len(calls)
@@ -187,20 +209,6 @@ def main():
         for j, (name, _) in enumerate(calls):
             ts = sorted(evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps))
             breakdown[name] = {"median_us": ts[len(ts) // 2] * 1e3, "min_us": ts[0] * 1e3}
-        sb = 2 if w.dtype == I.BF16 else 4
-        Tn, dm, E, k, C = w.T, w.d_model, w.E, w.k, w.capacity
-        kept_tok = int((L.slot >= 0).any(dim=1).sum().item())
-        alg = {   # algorithmic HBM bytes per call
-            "gate_logits": Tn * dm * sb + dm * E * 4 + Tn * E * 4,
-            "gate_route": Tn * E * 4 * 2 + 12 * Tn * k + 4 * Tn + 4 * Tn * k + 4 * E * C + 8 * E,
-            "dispatch": kept_tok * dm * sb + 4 * E * C + M * dm * sb,
-            "combine_fwd": M * dm * sb + 12 * Tn * k + Tn * dm * sb,
-            "combine_bwd": Tn * dm * sb + M * dm * sb + M * dm * sb + 4 * Tn * k,
-            "dispatch_bwd": M * dm * sb + 8 * Tn * k + Tn * dm * sb,
-            "gate_bwd": Tn * E * 4 * 2 + 16 * Tn * k,
-            "aux_loss": Tn * E * 4 + 4 * Tn * k,
-            "gate_logits_bwd": 2 * Tn * dm * sb + Tn * E * 4 + Tn * dm * sb + dm * E * 8,
-        }
         for name, b in alg.items():
             if name not in breakdown:
                 continue
@@ -218,7 +226,7 @@ def main():
             print(f"[breakdown] {name:16s} " + " ".join(f"{k}={val:.4g}" for k, val in v.items()), file=sys.stderr)
 
     out = {
-        "metric": "MoE layer fwd+bwd tokens/sec on 1 MI355X",
+        "metric": "MoE layer fwd+bwd tokens/sec on 1 MI355X; expert-GEMM MFMA util; route HBM GB/s",
         "value": w.T / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1,
@@ -239,6 +247,10 @@ def main():
                    "expert_demand_max": int(L.expert_demand.max().item()),
                    "expert_demand_min": int(L.expert_demand.min().item())},
         "roofline": roofline,
+        # the metric's other two parts: MFMA utilisation of the expert GEMMs = roofline.frac; achieved
+        # algorithmic HBM rate of the route / dispatch / combine calls (HIP events inside the timed region)
+        "expert_gemm_mfma_util": roofline["frac"],
+        "hbm_calls": hbm,
     }
     if breakdown is not None:
         out["breakdown"] = breakdown
