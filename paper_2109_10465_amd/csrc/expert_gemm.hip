@@ -265,14 +265,20 @@ __device__ __forceinline__ void act_both(float z, float& h, float& a) {
     a = cdf + zpdf;
 }
 
-// One row vector of the output tile: o = element offset, v = 4 accumulators,
-// aux = the 4 saved derivatives (EPI_MUL only).
+// Output of one tile: raw buffer descriptors over the expert's rows in use, so that
+// rows >= m_lim fall outside the range and their stores are dropped (no branches).
+struct TileOut {
+    __amdgpu_buffer_rsrc_t o0, o1, ax;
+};
+
+// One row vector of the output tile: off = byte offset inside the expert's output
+// (BUF_OOB for a column beyond N), o = element index in the whole tensor (for the
+// dropout noise), v = 4 accumulators, aux = the 4 saved derivatives (EPI_MUL only).
 template <typename T, int EPI, int ACT>
-__device__ __forceinline__ void epilogue4(const GemmArgs& p, size_t o, float (&v)[4],
-                                          typename Vec4io<T>::raw aux) {
-    typedef typename Vec4io<T>::raw raw;
+__device__ __forceinline__ void epilogue4(const GemmArgs& p, const TileOut& to, uint32_t off, size_t o,
+                                          float (&v)[4], typename Vec4io<T>::raw aux) {
     if constexpr (EPI == EPI_STORE) {
-        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(v);
+        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(v));
     } else if constexpr (EPI == EPI_H_DACT) {
         float h[4], a[4];
 #pragma unroll
@@ -287,21 +293,21 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& p, size_t o, float (&v
                 a[i] *= sc;     // backward needs no knowledge of it
             }
         }
-        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(a);
-        *reinterpret_cast<raw*>((T*)p.out1 + o) = Vec4io<T>::pack(h);
+        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(a));
+        Vec4buf<T>::store(to.o1, off, Vec4io<T>::pack(h));
     } else if constexpr (EPI == EPI_H) {
         float h[4], a[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) act_both<sizeof(T) == 2, ACT>(v[i], h[i], a[i]);   // the derivative is dead code here
-        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(h);
+        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(h));
     } else if constexpr (EPI == EPI_MUL) {
         float a[4];
         Vec4io<T>::unpack(aux, a);
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] *= a[i];
-        *reinterpret_cast<raw*>((T*)p.out0 + o) = Vec4io<T>::pack(v);
+        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(v));
     } else {
-        *reinterpret_cast<float4*>((float*)p.out0 + o) = make_float4(v[0], v[1], v[2], v[3]);
+        Vec4buf<float>::store(to.o0, off, make_float4(v[0], v[1], v[2], v[3]));
     }
 }
 
@@ -529,16 +535,22 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
         // the main loop; the later blocks are requested while earlier ones are written.
         constexpr int AUXB = EPI == EPI_MUL ? (TM < 2 ? TM : 2) : 1;
         raw aux[AUXB][EPI == EPI_MUL ? 4 : 1][EPI == EPI_MUL ? NIT : 1];
+        constexpr uint32_t OSZ = EPI == EPI_F32 ? 4u : (uint32_t)sizeof(T);   // bytes per output element
+        const size_t obytes = (size_t)m_lim * p.ldo * OSZ;                    // the expert's rows in use
+        TileOut to;
+        to.o0 = buf_rsrc((const char*)p.out0 + obase * OSZ, obytes);
+        to.o1 = buf_rsrc(EPI == EPI_H_DACT ? (const char*)p.out1 + obase * OSZ : nullptr, EPI == EPI_H_DACT ? obytes : 0);
+        to.ax = buf_rsrc(EPI == EPI_MUL ? (const char*)p.aux + obase * OSZ : nullptr, EPI == EPI_MUL ? obytes : 0);
+        const bool col_ok = ncol < p.N;
+        // byte offset of this lane's row vector in row m of the expert's output; a row
+        // >= m_lim lies beyond the descriptor's range by itself
+        auto out_off = [&](int m) { return col_ok ? (uint32_t)(((size_t)m * p.ldo + ncol) * OSZ) : BUF_OOB; };
         auto fetch_aux = [&](int buf, int i) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
 #pragma unroll
-                for (int it = 0; it < NIT; ++it) {
-                    const int m = mrow + i * 32 + q * 8 + it * RPI;
-                    aux[buf][q][it] = (m < m_lim && ncol < p.N)
-                        ? *reinterpret_cast<const raw*>((const T*)p.aux + obase + (size_t)m * p.ldo + ncol)
-                        : Vec4io<T>::zero();
-                }
+                for (int it = 0; it < NIT; ++it)
+                    aux[buf][q][it] = Vec4buf<T>::load(to.ax, out_off(mrow + i * 32 + q * 8 + it * RPI));
         };
         if constexpr (EPI == EPI_MUL) {
 #pragma unroll
@@ -612,40 +624,60 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
 
         // ---- epilogue: accumulators -> wave-private LDS strip -> row vectors --------
         // accumulator element v of lane l in a 32x32 tile: column l%32,
-        // row 8*(v/4) + 4*(l/32) + v%4; strip s = (i, q) holds rows i*32 + 8q .. +7
+        // row 8*(v/4) + 4*(l/32) + v%4; strip s = (i, q) = (s/4, s%4) holds rows i*32 + 8q .. +7.
+        // LDS operations of a wave execute in order, so strip s+1 is written and read
+        // back (into the other register set) before the vectors of strip s are used:
+        // the LDS round trip of every strip hides behind the previous strip's work.
+        constexpr int NSTRIP = 4 * TM;
+        auto write_strip = [&](int s_) {
+            const int i = s_ >> 2, q = s_ & 3;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+                for (int r = 0; r < 4; ++r) strip[(4 * g + r) * ELD + j * 32 + l32] = acc[i][j][4 * q + r];
+        };
+        auto read_strip = [&](float4 (&w)[NIT]) {
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+            for (int it = 0; it < NIT; ++it) w[it] = *reinterpret_cast<const float4*>(strip + (er + it * RPI) * ELD + ec);
+        };
+        constexpr bool ROLLED = EPI == EPI_H_DACT || EPI == EPI_H;   // long per-vector code: kept in a rolled loop
+        float4 w[ROLLED ? 1 : 2][NIT];
+        write_strip(0);
+        if constexpr (!ROLLED) read_strip(w[0]);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        strip[(4 * g + r) * ELD + j * 32 + l32] = acc[i][j][4 * q + r];
-                const int m_strip = mrow + i * 32 + q * 8;
-                if constexpr (EPI == EPI_H_DACT || EPI == EPI_H) {
+        for (int s_ = 0; s_ < NSTRIP; ++s_) {
+            const int i = s_ >> 2, q = s_ & 3;
+            const int m_strip = mrow + i * 32 + q * 8;
+            if constexpr (ROLLED) {
+                // one copy of the activation code per strip; the next vector is read from
+                // LDS before the current one is worked on (carried in registers, no arrays)
+                float4 cur = *reinterpret_cast<const float4*>(strip + er * ELD + ec);
 #pragma unroll 1
-                    for (int it = 0; it < NIT; ++it) {  // rolled: one copy of the activation code per strip
-                        const float4 w = *reinterpret_cast<const float4*>(strip + (er + it * RPI) * ELD + ec);
-                        float v[4] = {w.x, w.y, w.z, w.w};
-                        const int m = m_strip + it * RPI;
-                        if (m < m_lim && ncol < p.N)
-                            epilogue4<T, EPI, ACT>(p, obase + (size_t)m * p.ldo + ncol, v, Vec4io<T>::zero());
-                    }
-                } else {
+                for (int it = 0; it < NIT; ++it) {
+                    const int itn = it + 1 < NIT ? it + 1 : it;
+                    const float4 nxt = *reinterpret_cast<const float4*>(strip + (er + itn * RPI) * ELD + ec);
+                    float v[4] = {cur.x, cur.y, cur.z, cur.w};
+                    const int m = m_strip + it * RPI;
+                    epilogue4<T, EPI, ACT>(p, to, out_off(m), obase + (size_t)m * p.ldo + ncol, v, Vec4io<T>::zero());
+                    cur = nxt;
+                }
+                if (s_ + 1 < NSTRIP) write_strip(s_ + 1);
+            } else {
+                if (s_ + 1 < NSTRIP) {
+                    write_strip(s_ + 1);
+                    read_strip(w[(s_ + 1) & 1]);
+                }
 #pragma unroll
-                    for (int it = 0; it < NIT; ++it) {
-                        const float4 w = *reinterpret_cast<const float4*>(strip + (er + it * RPI) * ELD + ec);
-                        float v[4] = {w.x, w.y, w.z, w.w};
-                        const int m = m_strip + it * RPI;
-                        if (m < m_lim && ncol < p.N)
-                            epilogue4<T, EPI, ACT>(p, obase + (size_t)m * p.ldo + ncol, v,
-                                                   aux[EPI == EPI_MUL ? i % AUXB : 0][EPI == EPI_MUL ? q : 0][EPI == EPI_MUL ? it : 0]);
-                    }
+                for (int it = 0; it < NIT; ++it) {
+                    const float4 x4 = w[s_ & 1][it];
+                    float v[4] = {x4.x, x4.y, x4.z, x4.w};
+                    const int m = m_strip + it * RPI;
+                    epilogue4<T, EPI, ACT>(p, to, out_off(m), 0, v,
+                                           aux[EPI == EPI_MUL ? i % AUXB : 0][EPI == EPI_MUL ? q : 0][EPI == EPI_MUL ? it : 0]);
                 }
             }
             if constexpr (EPI == EPI_MUL) {
-                if (i + AUXB < TM) fetch_aux(i % AUXB, i + AUXB);   // the buffer just used is free again
+                if (q == 3 && i + AUXB < TM) fetch_aux(i % AUXB, i + AUXB);   // the buffer just used is free again
             }
         }
         more = cw.next(p);
