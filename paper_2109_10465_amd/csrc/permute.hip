@@ -4,11 +4,13 @@
 // per row, fp32 math, no atomics (each output row has exactly one writer).
 #include "moe_common.h"
 
+#ifndef ROWS_PER_WG
 #define ROWS_PER_WG 4  // one wave per row, 4 waves per workgroup
+#endif
 
 // xd[e,s,:] = x[slot_src[e,s]/k, :]   for s < expert_count[e]
 template <typename T>
-__global__ __launch_bounds__(256) void dispatch_kernel(int d, int k, int C, int n_rows,
+__global__ __launch_bounds__(64 * ROWS_PER_WG) void dispatch_kernel(int d, int k, int C, int n_rows,
                                                        const T* __restrict__ x,
                                                        const int32_t* __restrict__ slot_src,
                                                        const int32_t* __restrict__ expert_count,
@@ -27,7 +29,7 @@ __global__ __launch_bounds__(256) void dispatch_kernel(int d, int k, int C, int 
 
 // y[t,:] = sum_j [slot>=0] g_j * yd[e_j, slot_j, :]
 template <typename T>
-__global__ __launch_bounds__(256) void combine_fwd_kernel(int Tn, int d, int k, int C,
+__global__ __launch_bounds__(64 * ROWS_PER_WG) void combine_fwd_kernel(int Tn, int d, int k, int C,
                                                           const T* __restrict__ yd,
                                                           const int32_t* __restrict__ expert_idx,
                                                           const int32_t* __restrict__ slot,
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(256) void combine_fwd_kernel(int Tn, int d, int k, 
 
 // dyd[e,s,:] = g_j * dy[t,:];  dgate_w[t,j] = <dy[t,:], yd[e,s,:]>
 template <typename T>
-__global__ __launch_bounds__(256) void combine_bwd_kernel(int Tn, int d, int k, int C,
+__global__ __launch_bounds__(64 * ROWS_PER_WG) void combine_bwd_kernel(int Tn, int d, int k, int C,
                                                           const T* __restrict__ dy,
                                                           const T* __restrict__ yd,
                                                           const int32_t* __restrict__ expert_idx,
@@ -124,10 +126,10 @@ extern "C" int moe_dispatch(const moe_shape* shape, const void* x, const int32_t
     const int grid = ceil_div(n_rows, ROWS_PER_WG);
     hipStream_t st = (hipStream_t)stream;
     if (shape->dtype == MOE_BF16)
-        dispatch_kernel<bf16_t><<<grid, 256, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows,
+        dispatch_kernel<bf16_t><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows,
                                                       (const bf16_t*)x, slot_src, expert_count, (bf16_t*)xd);
     else
-        dispatch_kernel<float><<<grid, 256, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows,
+        dispatch_kernel<float><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows,
                                                      (const float*)x, slot_src, expert_count, (float*)xd);
     return launch_status();
 }
@@ -141,10 +143,10 @@ extern "C" int moe_combine_fwd(const moe_shape* shape, const void* yd, const int
     const int grid = ceil_div(shape->T, ROWS_PER_WG);
     hipStream_t st = (hipStream_t)stream;
     if (shape->dtype == MOE_BF16)
-        combine_fwd_kernel<bf16_t><<<grid, 256, 0, st>>>(shape->T, shape->d_model, shape->k, shape->capacity,
+        combine_fwd_kernel<bf16_t><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->T, shape->d_model, shape->k, shape->capacity,
                                                          (const bf16_t*)yd, expert_idx, slot, gate_w_or_null, (bf16_t*)y);
     else
-        combine_fwd_kernel<float><<<grid, 256, 0, st>>>(shape->T, shape->d_model, shape->k, shape->capacity,
+        combine_fwd_kernel<float><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->T, shape->d_model, shape->k, shape->capacity,
                                                         (const float*)yd, expert_idx, slot, gate_w_or_null, (float*)y);
     return launch_status();
 }
@@ -158,11 +160,11 @@ extern "C" int moe_combine_bwd(const moe_shape* shape, const void* dy, const voi
     const int grid = ceil_div(shape->T, ROWS_PER_WG);
     hipStream_t st = (hipStream_t)stream;
     if (shape->dtype == MOE_BF16)
-        combine_bwd_kernel<bf16_t><<<grid, 256, 0, st>>>(shape->T, shape->d_model, shape->k, shape->capacity,
+        combine_bwd_kernel<bf16_t><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->T, shape->d_model, shape->k, shape->capacity,
                                                          (const bf16_t*)dy, (const bf16_t*)yd, expert_idx, slot, gate_w,
                                                          (bf16_t*)dyd, dgate_w);
     else
-        combine_bwd_kernel<float><<<grid, 256, 0, st>>>(shape->T, shape->d_model, shape->k, shape->capacity,
+        combine_bwd_kernel<float><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->T, shape->d_model, shape->k, shape->capacity,
                                                         (const float*)dy, (const float*)yd, expert_idx, slot, gate_w,
                                                         (float*)dyd, dgate_w);
     return launch_status();
