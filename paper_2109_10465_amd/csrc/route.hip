@@ -2,7 +2,7 @@
 // Random-Token-Selection priority (Sec. 5.1 "MoE setting", Sec. 3.1).
 //
 // Three kernels on one stream, all integer-exact and free of float atomics:
-//   1. gate_topk     one thread per token: top-k, softmax, gate weights; per
+//   1. gate_topk     a few lanes per token: top-k, softmax, gate weights; per
 //                    256-token chunk a histogram of (expert, choice) segments.
 //   2. route_place   every workgroup re-derives, from the chunk histograms, the
 //                    segment offsets and its own chunk's prefix (a few KB of L2
@@ -12,7 +12,8 @@
 //                    publishes segment offsets, expert_demand and expert_count.
 //   3. route_rank    rank inside a segment by counting the candidates that
 //                    precede it in (key descending, token ascending) order,
-//                    LDS-tiled; slot = rank (+ first-choice demand for j = 1).
+//                    LDS-tiled, four threads per candidate; slot = rank
+//                    (+ first-choice demand for j = 1).
 // Grouped token selection (Sec. 3.1) runs the same three kernels with one set
 // of segments per group of consecutive tokens and Cg = C / G slots per group
 // and expert; an expert's kept rows of successive groups are laid end to end.
@@ -22,6 +23,7 @@
 
 #define CHUNK 256       // tokens per histogram chunk (= per gate_topk / route_place workgroup)
 #define RANK_TILE 256   // candidates per route_rank workgroup
+#define RANK_PARTS 4    // threads per candidate: each counts over a quarter of every staged tile
 
 struct RouteWs {
     int32_t* hist;        // [nchunk][k*E] candidates per chunk and segment
@@ -64,99 +66,119 @@ __device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
 
 // LPT lanes share one token, 4 consecutive experts per lane (4*LPT >= E), so a
 // token's logits are read with one coalesced 16-byte load per lane and reduced
-// with log2(LPT) butterfly steps; a workgroup walks its 256-token chunk in LPT
-// rounds of 256/LPT tokens.
+// with log2(LPT) butterfly steps.  A workgroup of up to 1024 threads owns a
+// 256-token chunk and walks it in ROUNDS rounds of 256/ROUNDS tokens; the logits
+// of up to 8 rounds are requested before any of them is used, so the chunk costs
+// one memory latency, not one per round.
 template <int LPT>
-__global__ __launch_bounds__(CHUNK) void gate_topk_kernel(
+struct TopkGeom {
+    static constexpr int ROUNDS = CHUNK * LPT <= 1024 ? 1 : CHUNK * LPT / 1024;
+    static constexpr int THREADS = CHUNK * LPT / ROUNDS;
+    static constexpr int TPI = CHUNK / ROUNDS;                  // tokens per round
+    static constexpr int BATCH = ROUNDS < 8 ? ROUNDS : 8;       // rounds whose logits are in flight together
+};
+
+template <int LPT>
+__global__ __launch_bounds__(TopkGeom<LPT>::THREADS) void gate_topk_kernel(
     int T, int E, int k, const float* __restrict__ logits, float* __restrict__ probs,
     int32_t* __restrict__ expert_idx, float* __restrict__ gate_w, int32_t* __restrict__ hist) {
+    typedef TopkGeom<LPT> G;
     __shared__ int32_t s_hist[512];
     const int kE = k * E;
-    for (int i = threadIdx.x; i < kE; i += CHUNK) s_hist[i] = 0;
+    for (int i = threadIdx.x; i < kE; i += G::THREADS) s_hist[i] = 0;
     __syncthreads();
-    constexpr int TPI = CHUNK / LPT;  // tokens per round
     const int gl = threadIdx.x % LPT, slot = threadIdx.x / LPT;
     const int e4 = gl * 4;
     const bool vec = (E & 3) == 0;
-    for (int it = 0; it < LPT; ++it) {
-        const int t = blockIdx.x * CHUNK + it * TPI + slot;
-        const bool valid = t < T;   // uniform within a token's lane group
-        float l[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-        if (valid) {
-            const float* row = logits + (size_t)t * E;
-            if (vec) {
-                if (e4 < E) {
-                    const float4 q = *reinterpret_cast<const float4*>(row + e4);
-                    l[0] = q.x; l[1] = q.y; l[2] = q.z; l[3] = q.w;
-                }
-            } else {
+    for (int it0 = 0; it0 < G::ROUNDS; it0 += G::BATCH) {
+        float lq[G::BATCH][4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (e4 + i < E) l[i] = row[e4 + i];
-            }
-        }
-        // the lane's own best two (ascending ids, strict comparisons)
-        float v0 = -INFINITY, v1 = -INFINITY;
-        int i0 = 0x7fffffff, i1 = 0x7fffffff;
+        for (int u = 0; u < G::BATCH; ++u) {
+            const int t = blockIdx.x * CHUNK + (it0 + u) * G::TPI + slot;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int e = e4 + i;
-            if (e < E) {
-                if (better(l[i], e, v0, i0)) { v1 = v0; i1 = i0; v0 = l[i]; i0 = e; }
-                else if (better(l[i], e, v1, i1)) { v1 = l[i]; i1 = e; }
-            }
-        }
-#pragma unroll
-        for (int o = LPT / 2; o > 0; o >>= 1) {
-            const float w0 = __shfl_xor(v0, o, MOE_WAVE), w1 = __shfl_xor(v1, o, MOE_WAVE);
-            const int j0 = __shfl_xor(i0, o, MOE_WAVE), j1 = __shfl_xor(i1, o, MOE_WAVE);
-            if (better(w0, j0, v0, i0)) {
-                if (better(v0, i0, w1, j1)) { v1 = v0; i1 = i0; } else { v1 = w1; i1 = j1; }
-                v0 = w0; i0 = j0;
-            } else if (better(w0, j0, v1, i1)) {
-                v1 = w0; i1 = j0;
-            }
-        }
-        float ex[4], part = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            ex[i] = (valid && e4 + i < E) ? expf(l[i] - v0) : 0.0f;
-            part += ex[i];
-        }
-#pragma unroll
-        for (int o = LPT / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, MOE_WAVE);
-        const float sum = part;
-        if (valid) {
-            float* pr = probs + (size_t)t * E;
-            if (vec) {
-                if (e4 < E)
-                    *reinterpret_cast<float4*>(pr + e4) = make_float4(ex[0] / sum, ex[1] / sum, ex[2] / sum, ex[3] / sum);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (e4 + i < E) pr[e4 + i] = ex[i] / sum;
-            }
-            if (gl == 0) {
-                const float p0 = 1.0f / sum;   // = exp(0) / sum
-                if (k == 1) {
-                    expert_idx[t] = i0;
-                    gate_w[t] = p0;
-                    atomicAdd(&s_hist[i0], 1);
+            for (int i = 0; i < 4; ++i) lq[u][i] = -INFINITY;
+            if (t < T) {
+                const float* row = logits + (size_t)t * E;
+                if (vec) {
+                    if (e4 < E) {
+                        const float4 q = *reinterpret_cast<const float4*>(row + e4);
+                        lq[u][0] = q.x; lq[u][1] = q.y; lq[u][2] = q.z; lq[u][3] = q.w;
+                    }
                 } else {
-                    const float p1 = expf(v1 - v0) / sum;
-                    const float S = p0 + p1;
-                    expert_idx[2 * t] = i0;
-                    expert_idx[2 * t + 1] = i1;
-                    gate_w[2 * t] = p0 / S;
-                    gate_w[2 * t + 1] = p1 / S;
-                    atomicAdd(&s_hist[i0 * 2], 1);
-                    atomicAdd(&s_hist[i1 * 2 + 1], 1);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (e4 + i < E) lq[u][i] = row[e4 + i];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < G::BATCH; ++u) {
+            const int t = blockIdx.x * CHUNK + (it0 + u) * G::TPI + slot;
+            const bool valid = t < T;   // uniform within a token's lane group
+            const float(&l)[4] = lq[u];
+            // the lane's own best two (ascending ids, strict comparisons)
+            float v0 = -INFINITY, v1 = -INFINITY;
+            int i0 = 0x7fffffff, i1 = 0x7fffffff;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = e4 + i;
+                if (e < E) {
+                    if (better(l[i], e, v0, i0)) { v1 = v0; i1 = i0; v0 = l[i]; i0 = e; }
+                    else if (better(l[i], e, v1, i1)) { v1 = l[i]; i1 = e; }
+                }
+            }
+#pragma unroll
+            for (int o = LPT / 2; o > 0; o >>= 1) {
+                const float w0 = __shfl_xor(v0, o, MOE_WAVE), w1 = __shfl_xor(v1, o, MOE_WAVE);
+                const int j0 = __shfl_xor(i0, o, MOE_WAVE), j1 = __shfl_xor(i1, o, MOE_WAVE);
+                if (better(w0, j0, v0, i0)) {
+                    if (better(v0, i0, w1, j1)) { v1 = v0; i1 = i0; } else { v1 = w1; i1 = j1; }
+                    v0 = w0; i0 = j0;
+                } else if (better(w0, j0, v1, i1)) {
+                    v1 = w0; i1 = j0;
+                }
+            }
+            float ex[4], part = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ex[i] = (valid && e4 + i < E) ? expf(l[i] - v0) : 0.0f;
+                part += ex[i];
+            }
+#pragma unroll
+            for (int o = LPT / 2; o > 0; o >>= 1) part += __shfl_xor(part, o, MOE_WAVE);
+            const float sum = part;
+            if (valid) {
+                float* pr = probs + (size_t)t * E;
+                if (vec) {
+                    if (e4 < E)
+                        *reinterpret_cast<float4*>(pr + e4) = make_float4(ex[0] / sum, ex[1] / sum, ex[2] / sum, ex[3] / sum);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (e4 + i < E) pr[e4 + i] = ex[i] / sum;
+                }
+                if (gl == 0) {
+                    const float p0 = 1.0f / sum;   // = exp(0) / sum
+                    if (k == 1) {
+                        expert_idx[t] = i0;
+                        gate_w[t] = p0;
+                        atomicAdd(&s_hist[i0], 1);
+                    } else {
+                        const float p1 = expf(v1 - v0) / sum;
+                        const float S = p0 + p1;
+                        expert_idx[2 * t] = i0;
+                        expert_idx[2 * t + 1] = i1;
+                        gate_w[2 * t] = p0 / S;
+                        gate_w[2 * t + 1] = p1 / S;
+                        atomicAdd(&s_hist[i0 * 2], 1);
+                        atomicAdd(&s_hist[i1 * 2 + 1], 1);
+                    }
                 }
             }
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < kE; i += CHUNK) hist[(size_t)blockIdx.x * kE + i] = s_hist[i];
+    for (int i = threadIdx.x; i < kE; i += G::THREADS) hist[(size_t)blockIdx.x * kE + i] = s_hist[i];
 }
 
 // ---------------------------------------------------------------------------
@@ -188,28 +210,49 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
     const int kE = k * E;
     const int g = chunk / cpg, c_lo = g * cpg, c_hi = min(c_lo + cpg, nchunk);
     const bool leader = chunk == c_lo;      // publishes the group's tables
+    // this thread's token: requested first, used after the offsets are known
+    const int t = chunk * CHUNK + threadIdx.x;
+    const bool valid = t < T;
+    const float key = (valid && keys) ? keys[t] : 0.0f;
+    int ev[2] = {-1, -1}, rank[2] = {0, 0};
+    for (int j = 0; j < k; ++j) ev[j] = valid ? expert_idx[(size_t)t * k + j] : -1;
     for (int seg = threadIdx.x; seg < kE; seg += CHUNK) {
-        int tot = 0, pre = 0;
-        int c = c_lo;
-        for (; c + 8 <= c_hi; c += 8) {   // 8 independent loads in flight
-            int v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = hist[(size_t)(c + u) * kE + seg];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                pre += c + u < chunk ? v[u] : 0;
-                tot += v[u];
-            }
-        }
-        for (; c < c_hi; ++c) {
-            const int v = hist[(size_t)c * kE + seg];
-            pre += c < chunk ? v : 0;
-            tot += v;
-        }
-        s_tot[seg] = tot;
-        s_base[seg] = pre;
+        s_tot[seg] = 0;
+        s_base[seg] = 0;
 #pragma unroll
         for (int w = 0; w < CHUNK / 64; ++w) s_wcnt[w][seg] = 0;
+    }
+    __syncthreads();
+    {
+        // the group's histograms are one array [chunk][segment]: every thread sums a
+        // strided share of it (8 loads in flight) and adds its part with integer LDS
+        // atomics; entries of chunks before this one also count towards the prefix
+        const int32_t* gh = hist + (size_t)c_lo * kE;
+        const int n = (c_hi - c_lo) * kE, before = (chunk - c_lo) * kE;
+        const bool fixed_seg = CHUNK % kE == 0;   // then a thread always meets the same segment
+        int tot = 0, pre = 0;
+        for (int i0 = threadIdx.x; i0 < n; i0 += 8 * CHUNK) {
+            int v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = i0 + u * CHUNK < n ? gh[i0 + u * CHUNK] : 0;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = i0 + u * CHUNK;
+                if (fixed_seg) {
+                    tot += v[u];
+                    pre += idx < before ? v[u] : 0;
+                } else if (idx < n && v[u]) {
+                    const int seg = idx % kE;
+                    atomicAdd(&s_tot[seg], v[u]);
+                    if (idx < before) atomicAdd(&s_base[seg], v[u]);
+                }
+            }
+        }
+        if (fixed_seg) {
+            const int seg = threadIdx.x % kE;
+            if (tot) atomicAdd(&s_tot[seg], tot);
+            if (pre) atomicAdd(&s_base[seg], pre);
+        }
     }
     __syncthreads();
     if (leader && threadIdx.x < E) {
@@ -277,21 +320,21 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
         }
     }
     __syncthreads();
-    const int t = chunk * CHUNK + threadIdx.x;
-    const bool valid = t < T;
-    const float key = (valid && keys) ? keys[t] : 0.0f;
-    int ev[2] = {-1, -1}, rank[2] = {0, 0};
+    // rank among the wave's tokens with the same (expert, choice): the set of such
+    // lanes is the intersection, over the bits of the expert id, of the lanes that
+    // agree with this lane on that bit (one ballot per bit, no lane exchange)
+    const int nbits = E > 1 ? 32 - __clz(E - 1) : 0;
     for (int j = 0; j < k; ++j) {
-        const int e = valid ? expert_idx[(size_t)t * k + j] : -1;
-        ev[j] = e;
-        unsigned long long todo = __ballot(valid);
-        while (todo) {  // one round per distinct expert among the wave's 64 tokens
-            const int leader = __ffsll((long long)todo) - 1;
-            const int le = __shfl(e, leader, MOE_WAVE);
-            const unsigned long long same = __ballot(valid && e == le);
-            if (valid && e == le) rank[j] = __popcll(same & ((1ull << lane) - 1ull));
-            if (lane == leader) s_wcnt[wave][le * k + j] = __popcll(same);
-            todo &= ~same;
+        const int e = ev[j];
+        unsigned long long same = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (e >> b) & 1;
+            const unsigned long long m = __ballot(valid && bit);
+            same &= bit ? m : ~m;
+        }
+        if (valid) {
+            rank[j] = __popcll(same & ((1ull << lane) - 1ull));
+            if (rank[j] == 0) s_wcnt[wave][e * k + j] = __popcll(same);
         }
     }
     __syncthreads();
@@ -309,68 +352,100 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
 // ---------------------------------------------------------------------------
 // 3. rank inside the segment, slots, slot_src
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(RANK_TILE) void route_rank_kernel(
+__global__ __launch_bounds__(RANK_TILE * RANK_PARTS) void route_rank_kernel(
     int E, int k, int C, int Cg, int tiles_per_group, int has_keys, const int32_t* __restrict__ seg_start_all,
     const int32_t* __restrict__ tile_start_all, const int32_t* __restrict__ goff,
     const int32_t* __restrict__ expert_count, const int32_t* __restrict__ seg_tok,
     const float* __restrict__ seg_key, int32_t* __restrict__ slot, int32_t* __restrict__ slot_src) {
-    __shared__ float s_key[RANK_TILE];
-    __shared__ int s_seg;
+    constexpr int NT = RANK_TILE * RANK_PARTS, Q = RANK_TILE / RANK_PARTS;
+    __shared__ __align__(16) float s_key[2][RANK_TILE];
+    __shared__ int s_cnt[RANK_PARTS][RANK_TILE];
+    __shared__ int s_info[5];   // segment, its start and end, its first tile, start of the segment before it
     const int kE = k * E;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & (RANK_TILE - 1);          // candidate inside the tile
+    const int part = threadIdx.x / RANK_TILE;               // wave-uniform
     const int grp = blockIdx.x / tiles_per_group;
     const int b = blockIdx.x - grp * tiles_per_group;       // tile inside the group
     const int32_t* seg_start = seg_start_all + (size_t)grp * (kE + 1);
     const int32_t* tile_start = tile_start_all + (size_t)grp * (kE + 1);
     // segment owning tile b: the one with tile_start[seg] <= b < tile_start[seg+1]
-    // (empty segments have an empty range); found by all threads in parallel
-    if (tid == 0) s_seg = -1;
+    // (empty segments have an empty range); found by all threads in parallel, each
+    // fetching what the owner will need in the same round of loads
+    if (threadIdx.x == 0) s_info[0] = -1;
     __syncthreads();
-    for (int sg = tid; sg < kE; sg += RANK_TILE)
-        if (tile_start[sg] <= b && b < tile_start[sg + 1]) s_seg = sg;
+    for (int sg = threadIdx.x; sg < kE; sg += NT) {
+        const int t0 = tile_start[sg], t1 = tile_start[sg + 1];
+        const int a0 = seg_start[sg], a1 = seg_start[sg + 1];
+        const int ap = sg > 0 ? seg_start[sg - 1] : 0;
+        if (t0 <= b && b < t1) {
+            s_info[0] = sg; s_info[1] = a0; s_info[2] = a1; s_info[3] = t0; s_info[4] = ap;
+        }
+    }
+    // unused slots (independent of the ranking; its loads overlap the search above)
+    const int total = E * C;
+    for (int idx = blockIdx.x * NT + threadIdx.x; idx < total; idx += gridDim.x * NT) {
+        const int e = idx / C, sl = idx - e * C;
+        if (sl >= expert_count[e]) slot_src[idx] = -1;
+    }
     __syncthreads();
-    if (s_seg >= 0) {
-        const int seg = s_seg;
-        const int s0 = seg_start[seg], s1 = seg_start[seg + 1];
-        const int own0 = s0 + (b - tile_start[seg]) * RANK_TILE;
-        const int p = own0 + tid;
-        const bool valid = p < s1;
-        int cnt = p - s0;  // position priority: candidates are stored in token order
-        if (has_keys) {
-            const float mine = valid ? seg_key[p] : 0.0f;
-            cnt = 0;
-            for (int q0 = s0; q0 < s1; q0 += RANK_TILE) {
-                __syncthreads();
-                s_key[tid] = q0 + tid < s1 ? seg_key[q0 + tid] : -INFINITY;
-                __syncthreads();
-                if (q0 < own0) {          // earlier tokens: equal keys precede
-#pragma unroll 8
-                    for (int i = 0; i < RANK_TILE; ++i) cnt += s_key[i] >= mine;
-                } else if (q0 > own0) {   // later tokens: only strictly larger keys precede
-#pragma unroll 8
-                    for (int i = 0; i < RANK_TILE; ++i) cnt += s_key[i] > mine;
-                } else {
-#pragma unroll 8
-                    for (int i = 0; i < RANK_TILE; ++i)
-                        cnt += (s_key[i] > mine) || (s_key[i] == mine && i < tid);
+    if (s_info[0] < 0) return;   // uniform: a spare tile
+    const int seg = s_info[0], s0 = s_info[1], s1 = s_info[2];
+    const int own0 = s0 + (b - s_info[3]) * RANK_TILE;
+    const int p = own0 + tid;
+    const bool valid = p < s1;
+    const int e = seg / k, j = seg - e * k;
+    // everything the result needs is requested before the ranking starts
+    const int tok = (valid && part == 0) ? seg_tok[p] : 0;
+    const int row0 = goff[(size_t)grp * E + e];             // earlier groups' rows come first
+    int cnt = p - s0;  // position priority: candidates are stored in token order
+    if (has_keys) {
+        const float mine = valid ? seg_key[p] : 0.0f;
+        cnt = 0;
+        float nxt = (part == 0 && s0 + tid < s1) ? seg_key[s0 + tid] : -INFINITY;
+        int buf = 0;
+        for (int q0 = s0; q0 < s1; q0 += RANK_TILE, buf ^= 1) {
+            if (part == 0) s_key[buf][tid] = nxt;   // the other buffer may still be read by slower waves
+            __syncthreads();
+            const int qn = q0 + RANK_TILE + tid;
+            nxt = (part == 0 && qn < s1) ? seg_key[qn] : -INFINITY;   // in flight under the counting
+            const float4* kk = reinterpret_cast<const float4*>(s_key[buf] + part * Q);
+            if (q0 < own0) {          // earlier tokens: equal keys precede
+#pragma unroll 4
+                for (int i = 0; i < Q / 4; ++i) {
+                    const float4 c4 = kk[i];
+                    cnt += (c4.x >= mine) + (c4.y >= mine) + (c4.z >= mine) + (c4.w >= mine);
+                }
+            } else if (q0 > own0) {   // later tokens: only strictly larger keys precede
+#pragma unroll 4
+                for (int i = 0; i < Q / 4; ++i) {
+                    const float4 c4 = kk[i];
+                    cnt += (c4.x > mine) + (c4.y > mine) + (c4.z > mine) + (c4.w > mine);
+                }
+            } else {
+#pragma unroll 4
+                for (int i = 0; i < Q / 4; ++i) {
+                    const float4 c4 = kk[i];
+                    const int i4 = part * Q + 4 * i;
+                    cnt += (c4.x > mine || (c4.x == mine && i4 < tid)) + (c4.y > mine || (c4.y == mine && i4 + 1 < tid)) +
+                           (c4.z > mine || (c4.z == mine && i4 + 2 < tid)) + (c4.w > mine || (c4.w == mine && i4 + 3 < tid));
                 }
             }
         }
-        if (valid) {
-            const int e = seg / k, j = seg - e * k;
-            const int base = j == 1 ? s0 - seg_start[seg - 1] : 0;  // first choices go first
-            const int rank = base + cnt;                            // inside (group, expert)
-            const int cand = seg_tok[p] * k + j;
-            const int row = goff[(size_t)grp * E + e] + rank;       // earlier groups' rows come first
-            slot[cand] = rank < Cg ? row : -1;
-            if (rank < Cg) slot_src[(size_t)e * C + row] = cand;
+        s_cnt[part][tid] = cnt;
+        __syncthreads();
+        if (part == 0) {
+            cnt = 0;
+#pragma unroll
+            for (int q = 0; q < RANK_PARTS; ++q) cnt += s_cnt[q][tid];
         }
     }
-    // unused slots
-    const int total = E * C;
-    for (int idx = blockIdx.x * RANK_TILE + tid; idx < total; idx += gridDim.x * RANK_TILE) {
-        const int e = idx / C, sl = idx - e * C;
-        if (sl >= expert_count[e]) slot_src[idx] = -1;
+    if (valid && part == 0) {
+        const int base = j == 1 ? s0 - s_info[4] : 0;           // first choices go first
+        const int rank = base + cnt;                            // inside (group, expert)
+        const int cand = tok * k + j;
+        const int row = row0 + rank;
+        slot[cand] = rank < Cg ? row : -1;
+        if (rank < Cg) slot_src[(size_t)e * C + row] = cand;
     }
 }
 
@@ -392,7 +467,7 @@ static int route_impl(const moe_shape* shape, int G, const float* logits, const 
     const int nchunk = n_chunks(shape);
     const int cpg = G == 1 ? nchunk : T / G / CHUNK;    // chunks per group
     const int Cg = C / G;
-#define GATE(LPT) gate_topk_kernel<LPT><<<nchunk, CHUNK, 0, st>>>(T, E, k, logits, probs, expert_idx, gate_w, r.hist)
+#define GATE(LPT) gate_topk_kernel<LPT><<<nchunk, TopkGeom<LPT>::THREADS, 0, st>>>(T, E, k, logits, probs, expert_idx, gate_w, r.hist)
     if (E <= 4) GATE(1); else if (E <= 8) GATE(2); else if (E <= 16) GATE(4); else if (E <= 32) GATE(8);
     else if (E <= 64) GATE(16); else if (E <= 128) GATE(32); else GATE(64);
 #undef GATE
@@ -401,7 +476,7 @@ static int route_impl(const moe_shape* shape, int G, const float* logits, const 
                                                  expert_demand, r.seg_tok, r.seg_key);
     const int Tg = G == 1 ? T : T / G;
     const int tiles_per_group = ceil_div(Tg * k, RANK_TILE) + k * E;
-    route_rank_kernel<<<G * tiles_per_group, RANK_TILE, 0, st>>>(E, k, C, Cg, tiles_per_group,
+    route_rank_kernel<<<G * tiles_per_group, RANK_TILE * RANK_PARTS, 0, st>>>(E, k, C, Cg, tiles_per_group,
                                                                  rts_keys_or_null != nullptr, r.seg_start,
                                                                  r.tile_start, r.goff, expert_count, r.seg_tok,
                                                                  r.seg_key, slot, slot_src);
