@@ -33,7 +33,7 @@ __device__ __forceinline__ void load8<float>(__amdgpu_buffer_rsrc_t rs, uint32_t
 }
 
 template <typename T, int NB, bool JIT>   // JIT: gate jitter on (a separate instance keeps the plain one lean)
-__global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
+__global__ __launch_bounds__(64 * GLM_KSPLIT, NB == 1 ? 4 : 2) void gate_logits_kernel(
     int Tn, int d, int E, const T* __restrict__ x, const float* __restrict__ Wg,
     const float* __restrict__ bias, float* __restrict__ logits, float jitter_eps, uint64_t seed) {
     constexpr int GRP = NB <= 2 ? 8 : 4;   // 16-deep blocks whose loads are in flight together
@@ -52,13 +52,20 @@ __global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+    // bf16 activations (no jitter): x goes to the bf16 matrix pipe as loaded and Wg as
+    // three bf16 parts that add up to it exactly, so the fp32 result is kept at a
+    // fraction of the fp32 pipe's time (one 32x32x16 step per part instead of eight 32x32x2)
+    constexpr bool SPLIT = sizeof(T) == 2 && !JIT;
     for (int b0 = b_lo; b0 < b_hi; b0 += GRP) {
-        float a[GRP][8];
+        float a[SPLIT ? 1 : GRP][8];
+        u32x4_buf_t araw[SPLIT ? GRP : 1];
 #pragma unroll
         for (int u = 0; u < GRP; ++u) {
             const int k = (b0 + u) * 16 + 8 * h;
             const bool ok = b0 + u < b_hi && k < d;     // rows beyond T fall outside rs_x
-            load8<T>(rs_x, ok ? (uint32_t)((r * d + k) * sizeof(T)) : BUF_OOB, a[u]);
+            const uint32_t off = ok ? (uint32_t)((r * d + k) * sizeof(T)) : BUF_OOB;
+            if constexpr (SPLIT) araw[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, off, 0, 0);
+            else load8<T>(rs_x, off, a[u]);
         }
         if constexpr (JIT) {   // the gate sees x * noise
 #pragma unroll
@@ -78,10 +85,20 @@ __global__ __launch_bounds__(64 * GLM_KSPLIT) void gate_logits_kernel(
                     bw[u][s_] = buf_load_f32(rs_w, ok ? (uint32_t)((k * E + nb * 32 + r) * 4) : BUF_OOB);
                 }
 #pragma unroll
-            for (int u = 0; u < GRP; ++u)
+            for (int u = 0; u < GRP; ++u) {
+                if constexpr (SPLIT) {
+                    bf16x8_hw_t w_hi, w_mid, w_lo;
+                    split3_bf16(bw[u], w_hi, w_mid, w_lo);
+                    const bf16x8_hw_t xa = __builtin_bit_cast(bf16x8_hw_t, araw[u]);
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_lo, acc[nb], 0, 0, 0);
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_mid, acc[nb], 0, 0, 0);
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_hi, acc[nb], 0, 0, 0);
+                } else {
 #pragma unroll
-                for (int s_ = 0; s_ < 8; ++s_)
-                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][s_], bw[u][s_], acc[nb], 0, 0, 0);
+                    for (int s_ = 0; s_ < 8; ++s_)
+                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][s_], bw[u][s_], acc[nb], 0, 0, 0);
+                }
+            }
         }
     }
     // accumulator element v of lane l: expert column l%32, token row 8*(v/4) + 4*(l/32) + v%4

@@ -130,6 +130,30 @@ template <> struct BufChunk<bf16_t> {
     }
 };
 
+// ---- fp32 operands on the bf16 matrix pipe ------------------------------------------
+// w = hi + mid + lo exactly, each part holding 8 significant bits cut off by
+// truncation (3 x 8 = the whole fp32 significand).  A product of a bf16 value with
+// each part is exact in fp32, so three bf16 MFMAs with fp32 accumulation multiply a
+// bf16 operand by an fp32 operand without loss; dropping `lo` leaves 16 bits.
+typedef __bf16 bf16x8_hw_t __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ void split3_bf16(const float (&w)[8], bf16x8_hw_t& hi, bf16x8_hw_t& mid, bf16x8_hw_t& lo) {
+    u32x4_buf_t qh, qm, ql;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float a = w[2 * i], b = w[2 * i + 1];
+        const uint32_t ah = __float_as_uint(a) & 0xffff0000u, bh = __float_as_uint(b) & 0xffff0000u;
+        const float a1 = a - __uint_as_float(ah), b1 = b - __uint_as_float(bh);
+        const uint32_t am = __float_as_uint(a1) & 0xffff0000u, bm = __float_as_uint(b1) & 0xffff0000u;
+        const float a2 = a1 - __uint_as_float(am), b2 = b1 - __uint_as_float(bm);
+        qh[i] = (ah >> 16) | bh;
+        qm[i] = (am >> 16) | bm;
+        ql[i] = (__float_as_uint(a2) >> 16) | (__float_as_uint(b2) & 0xffff0000u);
+    }
+    hi = __builtin_bit_cast(bf16x8_hw_t, qh);
+    mid = __builtin_bit_cast(bf16x8_hw_t, qm);
+    lo = __builtin_bit_cast(bf16x8_hw_t, ql);
+}
+
 template <typename T> struct Vec4buf;
 template <> struct Vec4buf<float> {
     __device__ static __forceinline__ float4 load(__amdgpu_buffer_rsrc_t r, uint32_t off) {
