@@ -252,6 +252,21 @@ int moe_gate_logits_bwd_jitter(const moe_shape* shape, const void* x, const floa
                                const float* dlogits, float jitter_eps, uint64_t seed, float* dWg,
                                void* dx_accum, void* ws, size_t ws_bytes, void* stream);
 
+/* The last two steps of the layer's backward as one call: dispatch's backward
+ * (moe_combine_fwd with NULL gate weights, the transpose of the dispatch of
+ * Sec. 3.1) and moe_gate_logits_bwd_jitter, without the intermediate dx ever
+ * being written and read back:
+ *   dWg[d_model,E] = (x .* noise)^T * dlogits                           (overwritten)
+ *   dx[t,:] = sum over kept choices j of dxd[expert_idx[t,j], slot[t,j], :]
+ *             + ((dlogits * Wg^T) .* noise)[t,:]                        (overwritten)
+ * dxd [E, capacity, d_model] and dx [T, d_model] have the activation type; the
+ * sum is formed in fp32 and rounded once.  jitter_eps = 0: no noise (seed unused).
+ * Needs workspace. */
+int moe_dispatch_gate_logits_bwd(const moe_shape* shape, const void* x, const float* Wg,
+                                 const float* dlogits, const void* dxd, const int32_t* expert_idx,
+                                 const int32_t* slot, float jitter_eps, uint64_t seed, float* dWg,
+                                 void* dx, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

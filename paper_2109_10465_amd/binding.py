@@ -20,6 +20,7 @@ EXPORTS = [
     "moe_gate_bwd", "moe_gate_logits_bwd", "moe_aux_loss", "moe_gate_bwd_aux",
     "moe_utilisation_accumulate", "moe_gate_route_grouped",
     "moe_gate_logits_jitter", "moe_gate_logits_bwd_jitter", "moe_expert_ffn_fwd_dropout",
+    "moe_dispatch_gate_logits_bwd",
 ]
 
 
@@ -70,6 +71,7 @@ def lib():
             "moe_gate_logits_jitter": [shp, vp, vp, vp, ctypes.c_float, ctypes.c_uint64, vp, vp],
             "moe_gate_logits_bwd_jitter": [shp, vp, vp, vp, ctypes.c_float, ctypes.c_uint64, vp, vp, vp, sz, vp],
             "moe_expert_ffn_fwd_dropout": [shp] + [vp] * 4 + [ctypes.c_float, ctypes.c_uint64] + [vp] * 4,
+            "moe_dispatch_gate_logits_bwd": [shp] + [vp] * 6 + [ctypes.c_float, ctypes.c_uint64, vp, vp, vp, sz, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -191,6 +193,15 @@ def moe_gate_logits_bwd_jitter(shape, x, Wg, dlogits, jitter_eps, seed, dWg, dx_
                                             int(seed), _p(dWg), _p(dx_accum), _p(ws),
                                             0 if ws is None else ws.numel() * ws.element_size(),
                                             _stream(stream)), "moe_gate_logits_bwd_jitter")
+
+
+def moe_dispatch_gate_logits_bwd(shape, x, Wg, dlogits, dxd, expert_idx, slot, jitter_eps, seed, dWg, dx, ws,
+                                 stream=None):
+    _check(lib().moe_dispatch_gate_logits_bwd(ctypes.byref(shape), _p(x), _p(Wg), _p(dlogits), _p(dxd),
+                                              _p(expert_idx), _p(slot),
+                                              float(jitter_eps), int(seed), _p(dWg), _p(dx), _p(ws),
+                                              0 if ws is None else ws.numel() * ws.element_size(),
+                                              _stream(stream)), "moe_dispatch_gate_logits_bwd")
 
 
 def moe_expert_ffn_fwd_dropout(shape, xd, expert_count, W1, W2, drop_p, seed, h_saved, dact_saved, yd,

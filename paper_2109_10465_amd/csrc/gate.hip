@@ -317,22 +317,28 @@ __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(int n, int nchunk,
 }
 
 // ---------------------------------------------------------------------------
-// dx[t,:] += dlogits[t,:] * Wg^T   on the fp32 matrix pipe
-// Workgroup: 32 tokens, 8 waves; wave w takes the 32-column blocks w, w+8, ...
-// of d.  The product is formed transposed, D[column][token], so that a lane's
-// accumulators (4 consecutive rows of D at 4 places) are 4 consecutive columns of
-// ONE token row (16 consecutive ones after a permutation of the tile's rows): dx
-// is updated in place with 16-byte accesses and no LDS.
-// A = Wg rows (column i, all experts), B = dlogits rows (token, all experts):
-// both are contiguous along the reduction, so a lane half reads its 16 experts
-// of a 32-expert block as 64 contiguous bytes (instruction s uses expert 16h+s).
+// dx[t,:] (+)= dlogits[t,:] * Wg^T   on the fp32 matrix pipe
+// Workgroup: 32 tokens, 4 waves; wave w takes the 64-column passes w, w+4, ...
+// of d (two 32x32 tiles, D[token][column]).  A = dlogits rows (token, all
+// experts), B = Wg rows (column i, all experts): both are contiguous along the
+// reduction, so a lane half reads its 16 experts of a 32-expert block as 64
+// contiguous bytes (instruction s uses expert 16h+s).  For bf16 activations the
+// result needs 8 bits only: both operands go to the bf16 matrix pipe as hi + lo
+// pairs (three 32x32x16 steps per 16 experts instead of sixteen 32x32x2 ones,
+// relative error 2^-15).  The tiles leave through a
+// wave-private LDS stage so that global accesses run along the row: 16 bytes per
+// lane, a whole 64-column row piece (128 or 256 bytes) per group of lanes.
+// GATHER: dx is not read; the value the product is added to is dispatch's
+// backward, the sum of the token's kept rows of dxd [E, C, d] (row slot[t,j] of
+// expert expert_idx[t,j]; slot < 0: dropped), fetched here so that this
+// intermediate never goes through memory.
 // ---------------------------------------------------------------------------
-template <bool VEC>
-__device__ __forceinline__ void load16(__amdgpu_buffer_rsrc_t rs, int row_elems, int e0, int E, float (&v)[16]) {
-    // 16 consecutive fp32 of one row starting at element e0 of the row (row_elems = row * E)
+template <bool VEC, int N>
+__device__ __forceinline__ void load_row_f32(__amdgpu_buffer_rsrc_t rs, int row_elems, int e0, int E, float (&v)[N]) {
+    // N consecutive fp32 of one row starting at element e0 of the row (row_elems = row * E)
     if constexpr (VEC) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
+        for (int c = 0; c < N / 4; ++c) {
             float q[4];
             BufChunk<float>::load(rs, e0 + 4 * c < E ? (uint32_t)((row_elems + e0 + 4 * c) * 4) : BUF_OOB, q);
 #pragma unroll
@@ -340,17 +346,30 @@ __device__ __forceinline__ void load16(__amdgpu_buffer_rsrc_t rs, int row_elems,
         }
     } else {
 #pragma unroll
-        for (int j = 0; j < 16; ++j)
+        for (int j = 0; j < N; ++j)
             v[j] = buf_load_f32(rs, e0 + j < E ? (uint32_t)((row_elems + e0 + j) * 4) : BUF_OOB);
     }
 }
 
-template <typename T, int EB, bool VEC>   // EB = 32-expert blocks (E <= 32*EB); VEC: E % 4 == 0
-__global__ __launch_bounds__(512) void gate_dx_kernel(int Tn, int d, int E,
-                                                      const float* __restrict__ dlogits,
-                                                      const float* __restrict__ Wg,
-                                                      T* __restrict__ dx, float jitter_eps, uint64_t seed) {
-    constexpr bool HOIST = EB <= 2;      // dlogits fragments stay in registers across column blocks
+#define GDX_WAVES 4
+#define GDX_COLS 64     // columns per wave pass
+
+template <typename T, int EB, bool VEC, bool GATHER>   // EB = 32-expert blocks (E <= 32*EB); VEC: E % 4 == 0
+__global__ __launch_bounds__(64 * GDX_WAVES) void gate_dx_kernel(int Tn, int d, int E, int k, int C,
+                                                                 const float* __restrict__ dlogits,
+                                                                 const float* __restrict__ Wg,
+                                                                 const T* __restrict__ dxd,
+                                                                 const int32_t* __restrict__ expert_idx,
+                                                                 const int32_t* __restrict__ slot,
+                                                                 T* __restrict__ dx, float jitter_eps, uint64_t seed) {
+    constexpr bool HOIST = EB <= 2;      // dlogits fragments stay in registers across passes
+    constexpr int LD = GDX_COLS + 4;     // floats per staged row (16-byte aligned, rows 4 apart on other banks)
+    constexpr int CN = Chunk<T>::N;      // elements per 16-byte piece
+    constexpr int LPR = GDX_COLS / CN;   // lanes per staged row
+    constexpr int RPI = 64 / LPR;        // rows per wave instruction
+    constexpr int NIT = 32 / RPI;        // row pieces per lane and pass
+    __shared__ __align__(16) float stage[GDX_WAVES][32][LD];
+    __shared__ int s_row[2][32];         // row of dxd behind each of the token's choices (-1: dropped)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, h = lane >> 5;
     const int t0 = blockIdx.x * 32;
@@ -358,54 +377,176 @@ __global__ __launch_bounds__(512) void gate_dx_kernel(int Tn, int d, int E,
     const __amdgpu_buffer_rsrc_t rs_dl = buf_rsrc(dlogits + (size_t)t0 * E, (size_t)rows_here * E * 4);
     const __amdgpu_buffer_rsrc_t rs_w = buf_rsrc(Wg, (size_t)d * E * 4);
     const __amdgpu_buffer_rsrc_t rs_dx = buf_rsrc(dx + (size_t)t0 * d, (size_t)rows_here * d * sizeof(T));
-    float bfr[HOIST ? EB : 1][16];
+    if constexpr (GATHER) {
+        if (threadIdx.x < 64) {
+            const int t = t0 + r;
+            int row = -1;
+            if (t < Tn && h < k) {
+                const int sl = slot[(size_t)t * k + h];
+                if (sl >= 0) row = expert_idx[(size_t)t * k + h] * C + sl;
+            }
+            s_row[h][r] = row;
+        }
+        __syncthreads();
+    }
+    constexpr bool SPLIT = sizeof(T) == 2;
+    float afr[(HOIST && !SPLIT) ? EB : 1][16];
+    bf16x8_hw_t a_hi[(HOIST && SPLIT) ? EB : 1][2], a_lo[(HOIST && SPLIT) ? EB : 1][2];
+    auto load_a = [&](int eb, int to) {   // the token row's fragments of expert block eb (rows beyond T read zeros)
+        if constexpr (SPLIT) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                float w8[8];
+                load_row_f32<VEC, 8>(rs_dl, r * E, eb * 32 + ks * 16 + 8 * h, E, w8);
+                split2_bf16(w8, a_hi[to][ks], a_lo[to][ks]);
+            }
+        } else {
+            load_row_f32<VEC, 16>(rs_dl, r * E, eb * 32 + 16 * h, E, afr[to]);
+        }
+    };
     if constexpr (HOIST) {
 #pragma unroll
-        for (int eb = 0; eb < EB; ++eb) load16<VEC>(rs_dl, r * E, eb * 32 + 16 * h, E, bfr[eb]);   // rows beyond T read zeros
+        for (int eb = 0; eb < EB; ++eb) load_a(eb, eb);
     }
-    const int ncb = (d + 31) / 32;
-    // Row m of the product tile stands for column i0 + pi(m) of the block, with
-    // pi(8q + 4h' + j) = 16h' + 4q + j: a lane's accumulator v (row 8(v/4) + 4h + v%4)
-    // is then column i0 + 16h + v, i.e. 16 CONSECUTIVE columns of its token row.
-    const int a_col = 16 * ((r >> 2) & 1) + 4 * (r >> 3) + (r & 3);   // pi(r): the Wg row this lane supplies
-    constexpr int CN = BufChunk<T>::N, NCH = 16 / CN;                 // 16-byte pieces of the lane's 16 columns
-    for (int cb = wave; cb < ncb; cb += 8) {
-        const int i0 = cb * 32;
-        const int c0 = i0 + 16 * h;
-        float cur[NCH][CN];
+    const int er = lane / LPR, ec = (lane - er * LPR) * CN;
+    float(*st)[LD] = stage[wave];
+    // What the product is added to does not depend on it: the 16-byte pieces of a
+    // pass are requested one pass ahead and stay packed until they are used.
+    constexpr int NSRC = GATHER ? 2 : 1;
+    int grow[NSRC][NIT];                 // GATHER: row of dxd per choice (-1: dropped)
+    if constexpr (GATHER) {
 #pragma unroll
-        for (int q = 0; q < NCH; ++q)   // d % 8 == 0: a piece is inside the row or wholly beyond it
-            BufChunk<T>::load(rs_dx, c0 + q * CN < d ? (uint32_t)((r * d + c0 + q * CN) * sizeof(T)) : BUF_OOB, cur[q]);
-        glm_f32x16 acc;
+        for (int it = 0; it < NIT; ++it) {
+            grow[0][it] = s_row[0][er + it * RPI];
+            grow[1][it] = k == 2 ? s_row[1][er + it * RPI] : -1;
+        }
+    }
+    auto request = [&](int i0, u32x4_buf_t (&q)[NSRC][NIT]) {
+        const int col = i0 + ec;
+        const bool ok = col < d;         // d % 8 == 0: a piece is inside the row or wholly beyond it
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+        for (int it = 0; it < NIT; ++it) {
+            if constexpr (GATHER) {
+                // a dropped choice (or a piece beyond d) reads a valid address and is masked
+                // out afterwards: every load is unconditional and inside the tensor
+                q[0][it] = *reinterpret_cast<const u32x4_buf_t*>(dxd + (size_t)max(grow[0][it], 0) * d + (ok ? col : 0));
+                if (k == 2)   // uniform
+                    q[1][it] = *reinterpret_cast<const u32x4_buf_t*>(dxd + (size_t)max(grow[1][it], 0) * d + (ok ? col : 0));
+            } else {
+                q[0][it] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rs_dx, ok ? (uint32_t)(((er + it * RPI) * d + col) * sizeof(T)) : BUF_OOB, 0, 0);
+            }
+        }
+    };
+    auto widen = [](u32x4_buf_t q, float (&v)[CN]) {
+        if constexpr (sizeof(T) == 2) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[2 * i] = __uint_as_float(q[i] << 16);
+                v[2 * i + 1] = __uint_as_float(q[i] & 0xffff0000u);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = __uint_as_float(q[i]);
+        }
+    };
+    u32x4_buf_t now[NSRC][NIT] = {}, ahead[NSRC][NIT] = {};
+    request(wave * GDX_COLS, now);
+    for (int i0 = wave * GDX_COLS; i0 < d; i0 += GDX_WAVES * GDX_COLS) {
+        const int col = i0 + ec;
+        const bool col_ok = col < d;
+        const int i0n = i0 + GDX_WAVES * GDX_COLS;
+        glm_f32x16 acc[2];
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[c][v] = 0.0f;
 #pragma unroll
         for (int eb = 0; eb < EB; ++eb) {
-            float afr[16];
-            load16<VEC>(rs_w, (i0 + a_col) * E, eb * 32 + 16 * h, E, afr);   // rows beyond d fall outside rs_w
-            if constexpr (!HOIST) load16<VEC>(rs_dl, r * E, eb * 32 + 16 * h, E, bfr[0]);
+            if constexpr (!HOIST) load_a(eb, 0);
+            const int ai = HOIST ? eb : 0;
+            // Wg (L2 resident) first, then the next pass's pieces: loads return in the
+            // order they were issued, and the MFMAs below must not wait for memory
+            float wfr[2][16];
 #pragma unroll
-            for (int s_ = 0; s_ < 16; ++s_)
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(afr[s_], bfr[HOIST ? eb : 0][s_], acc, 0, 0, 0);
+            for (int c = 0; c < 2; ++c) {   // rows beyond d fall outside rs_w
+                const int wrow = (i0 + 32 * c + r) * E;
+                if constexpr (SPLIT) {      // experts 8h.. and 16 + 8h.. of the block (k = 8h + s per 16-deep step)
+                    float lo8[8], hi8[8];
+                    load_row_f32<VEC, 8>(rs_w, wrow, eb * 32 + 8 * h, E, lo8);
+                    load_row_f32<VEC, 8>(rs_w, wrow, eb * 32 + 16 + 8 * h, E, hi8);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) { wfr[c][j] = lo8[j]; wfr[c][8 + j] = hi8[j]; }
+                } else {
+                    load_row_f32<VEC, 16>(rs_w, wrow, eb * 32 + 16 * h, E, wfr[c]);
+                }
+            }
+            if (eb == EB - 1 && i0n < d) request(i0n, ahead);    // uniform
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                if constexpr (SPLIT) {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        float w8[8];
+                        bf16x8_hw_t b_hi, b_lo;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) w8[j] = wfr[c][8 * ks + j];
+                        split2_bf16(w8, b_hi, b_lo);
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[ai][ks], b_hi, acc[c], 0, 0, 0);
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[ai][ks], b_lo, acc[c], 0, 0, 0);
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[ai][ks], b_hi, acc[c], 0, 0, 0);
+                    }
+                } else {
+#pragma unroll
+                    for (int s_ = 0; s_ < 16; ++s_)
+                        acc[c] = __builtin_amdgcn_mfma_f32_32x32x2f32(afr[ai][s_], wfr[c][s_], acc[c], 0, 0, 0);
+                }
+            }
         }
-        float inc[16];
+        // accumulator element v of lane l: column l%32, token row 8*(v/4) + 4*(l/32) + v%4
 #pragma unroll
-        for (int v = 0; v < 16; ++v) inc[v] = acc[v];
-        if (jitter_eps != 0.0f)     // the gate saw x * noise: d/dx carries the factor (uniform branch)
-            jitter_scale<16>(inc, (size_t)(t0 + r) * d + c0, jitter_eps, seed);
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int q = 0; q < NCH; ++q) {   // stores beyond T or d are dropped by the range check
+            for (int v = 0; v < 16; ++v) st[8 * (v >> 2) + 4 * h + (v & 3)][32 * c + r] = acc[c][v];
+        // LDS operations of a wave execute in order: the row pieces read below are complete
 #pragma unroll
-            for (int j = 0; j < CN; ++j) cur[q][j] += inc[q * CN + j];
-            BufChunk<T>::store(rs_dx, c0 + q * CN < d ? (uint32_t)((r * d + c0 + q * CN) * sizeof(T)) : BUF_OOB, cur[q]);
+        for (int it = 0; it < NIT; ++it) {
+            const int m = er + it * RPI;
+            float inc[CN];
+#pragma unroll
+            for (int q = 0; q < CN / 4; ++q) {
+                const float4 w4 = *reinterpret_cast<const float4*>(&st[m][ec + 4 * q]);
+                inc[4 * q] = w4.x; inc[4 * q + 1] = w4.y; inc[4 * q + 2] = w4.z; inc[4 * q + 3] = w4.w;
+            }
+            if (jitter_eps != 0.0f)     // the gate saw x * noise: d/dx carries the factor (uniform branch)
+                jitter_scale<CN>(inc, (size_t)(t0 + m) * d + col, jitter_eps, seed);
+            float add[CN];
+            widen(now[0][it], add);
+            if constexpr (GATHER) {
+                float add1[CN];
+                widen(now[1][it], add1);
+#pragma unroll
+                for (int j = 0; j < CN; ++j)
+                    inc[j] += (grow[0][it] >= 0 ? add[j] : 0.0f) + (grow[1][it] >= 0 ? add1[j] : 0.0f);
+            } else {
+#pragma unroll
+                for (int j = 0; j < CN; ++j) inc[j] += add[j];
+            }
+            // stores beyond T or d are dropped by the range check
+            BufChunk<T>::store(rs_dx, col_ok ? (uint32_t)((m * d + col) * sizeof(T)) : BUF_OOB, inc);
         }
+#pragma unroll
+        for (int q = 0; q < NSRC; ++q)
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) now[q][it] = ahead[q][it];
     }
 }
 
 template <typename T>
 static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const float* Wg,
-                                   const float* dlogits, float* dWg, void* dx, float* partial,
-                                   float eps, uint64_t seed, hipStream_t st) {
+                                   const float* dlogits, float* dWg, void* dx, const void* dxd,
+                                   const int32_t* expert_idx, const int32_t* slot, float* partial, float eps,
+                                   uint64_t seed, hipStream_t st) {
     const int tpc = gw_chunk_tokens(s);
     const int nch_used = ceil_div(s->T, tpc);
     dim3 grid(ceil_div(s->d_model, GW_COLS), nch_used, ceil_div(s->E, 32));
@@ -425,39 +566,51 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
     gate_dwg_reduce_kernel<<<ceil_div(n, 256), 256, 0, st>>>(n, nch_used, partial, dWg);
     if (dx) {
         const int grid_dx = ceil_div(s->T, 32);
-#define GDX(EB, VEC) gate_dx_kernel<T, EB, VEC><<<grid_dx, 512, 0, st>>>(s->T, s->d_model, s->E, dlogits, Wg, (T*)dx, eps, seed)
-#define GDXE(VEC) do { if (s->E <= 32) GDX(1, VEC); else if (s->E <= 64) GDX(2, VEC); \
-                       else if (s->E <= 128) GDX(4, VEC); else GDX(8, VEC); } while (0)
-        if (s->E % 4 == 0) GDXE(true); else GDXE(false);
+#define GDX(EB, VEC, GA) gate_dx_kernel<T, EB, VEC, GA><<<grid_dx, 64 * GDX_WAVES, 0, st>>>( \
+    s->T, s->d_model, s->E, s->k, s->capacity, dlogits, Wg, (const T*)dxd, expert_idx, slot, (T*)dx, eps, seed)
+#define GDXE(VEC, GA) do { if (s->E <= 32) GDX(1, VEC, GA); else if (s->E <= 64) GDX(2, VEC, GA); \
+                           else if (s->E <= 128) GDX(4, VEC, GA); else GDX(8, VEC, GA); } while (0)
+        if (dxd) { if (s->E % 4 == 0) GDXE(true, true); else GDXE(false, true); }
+        else     { if (s->E % 4 == 0) GDXE(true, false); else GDXE(false, false); }
 #undef GDXE
 #undef GDX
     }
 }
 
 static int gate_logits_bwd_impl(const moe_shape* shape, const void* x, const float* Wg, const float* dlogits,
-                                float eps, uint64_t seed, float* dWg, void* dx_accum, void* ws,
-                                size_t ws_bytes, void* stream) {
+                                float eps, uint64_t seed, float* dWg, void* dx_accum, const void* dxd,
+                                const int32_t* expert_idx, const int32_t* slot, void* ws, size_t ws_bytes,
+                                void* stream) {
     int rc = check_shape(shape);
     if (rc) return rc;
     if (!x || !Wg || !dlogits || !dWg) return MOE_ERR_NULL;
     if (!(eps >= 0.0f && eps < 1.0f)) return MOE_ERR_SHAPE;
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < gate_logits_bwd_ws_bytes(shape)) return MOE_ERR_WORKSPACE;
     if (shape->dtype == MOE_BF16)
-        launch_gate_logits_bwd<bf16_t>(shape, x, Wg, dlogits, dWg, dx_accum, (float*)ws, eps, seed, (hipStream_t)stream);
+        launch_gate_logits_bwd<bf16_t>(shape, x, Wg, dlogits, dWg, dx_accum, dxd, expert_idx, slot, (float*)ws, eps, seed, (hipStream_t)stream);
     else
-        launch_gate_logits_bwd<float>(shape, x, Wg, dlogits, dWg, dx_accum, (float*)ws, eps, seed, (hipStream_t)stream);
+        launch_gate_logits_bwd<float>(shape, x, Wg, dlogits, dWg, dx_accum, dxd, expert_idx, slot, (float*)ws, eps, seed, (hipStream_t)stream);
     return launch_status();
 }
 
 extern "C" int moe_gate_logits_bwd(const moe_shape* shape, const void* x, const float* Wg,
                                    const float* dlogits, float* dWg, void* dx_accum, void* ws,
                                    size_t ws_bytes, void* stream) {
-    return gate_logits_bwd_impl(shape, x, Wg, dlogits, 0.0f, 0, dWg, dx_accum, ws, ws_bytes, stream);
+    return gate_logits_bwd_impl(shape, x, Wg, dlogits, 0.0f, 0, dWg, dx_accum, nullptr, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 extern "C" int moe_gate_logits_bwd_jitter(const moe_shape* shape, const void* x, const float* Wg,
                                           const float* dlogits, float jitter_eps, uint64_t seed,
                                           float* dWg, void* dx_accum, void* ws, size_t ws_bytes,
                                           void* stream) {
-    return gate_logits_bwd_impl(shape, x, Wg, dlogits, jitter_eps, seed, dWg, dx_accum, ws, ws_bytes, stream);
+    return gate_logits_bwd_impl(shape, x, Wg, dlogits, jitter_eps, seed, dWg, dx_accum, nullptr, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+extern "C" int moe_dispatch_gate_logits_bwd(const moe_shape* shape, const void* x, const float* Wg,
+                                            const float* dlogits, const void* dxd, const int32_t* expert_idx,
+                                            const int32_t* slot, float jitter_eps, uint64_t seed, float* dWg,
+                                            void* dx, void* ws, size_t ws_bytes, void* stream) {
+    if (!dxd || !expert_idx || !slot || !dx) return MOE_ERR_NULL;
+    return gate_logits_bwd_impl(shape, x, Wg, dlogits, jitter_eps, seed, dWg, dx, dxd, expert_idx, slot, ws, ws_bytes,
+                                stream);
 }

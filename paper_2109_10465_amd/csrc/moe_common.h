@@ -154,6 +154,19 @@ __device__ __forceinline__ void split3_bf16(const float (&w)[8], bf16x8_hw_t& hi
     lo = __builtin_bit_cast(bf16x8_hw_t, ql);
 }
 
+// w ~ hi + lo with both parts rounded to nearest: |w - hi - lo| <= 2^-16 |w|
+__device__ __forceinline__ void split2_bf16(const float (&w)[8], bf16x8_hw_t& hi, bf16x8_hw_t& lo) {
+    u32x4_buf_t qh, ql;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t ph = pack_bf16x2(w[2 * i], w[2 * i + 1]);
+        ql[i] = pack_bf16x2(w[2 * i] - __uint_as_float(ph << 16), w[2 * i + 1] - __uint_as_float(ph & 0xffff0000u));
+        qh[i] = ph;
+    }
+    hi = __builtin_bit_cast(bf16x8_hw_t, qh);
+    lo = __builtin_bit_cast(bf16x8_hw_t, ql);
+}
+
 template <typename T> struct Vec4buf;
 template <> struct Vec4buf<float> {
     __device__ static __forceinline__ float4 load(__amdgpu_buffer_rsrc_t r, uint32_t off) {

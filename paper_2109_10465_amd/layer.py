@@ -106,15 +106,15 @@ class MoELayer:
                           self.dgate_w)
         B.moe_expert_ffn_bwd(s, self.dyd, self.xd, self.h, self.dact, self.expert_count, W1, W2,
                              self.dxd, self.dW1, self.dW2, self.ws)
-        # dispatch's backward = combine with unit weights
-        B.moe_combine_fwd(s, self.dxd, self.expert_idx, self.slot, None, self.dx)
         if self.aux_coef != 0.0:
             B.moe_gate_bwd_aux(s, self.dgate_w, self.probs, self.expert_idx, self.slot, self.first_frac,
                                self.aux_coef, self.dlogits)
         else:
             B.moe_gate_bwd(s, self.dgate_w, self.probs, self.expert_idx, self.slot, self.dlogits)
-        B.moe_gate_logits_bwd_jitter(s, x, Wg, self.dlogits, self.jitter_eps, self.seed, self.dWg, self.dx,
-                                     self.ws)
+        # dispatch's backward (combine with unit weights) and the gate projection's backward in one call
+        B.moe_dispatch_gate_logits_bwd(s, x, Wg, self.dlogits, self.dxd, self.expert_idx, self.slot,
+                                       self.jitter_eps, self.seed,
+                                       self.dWg, self.dx, self.ws)
         return self.dx, self.dWg, self.dW1, self.dW2
 
     def step(self, x, Wg, bias, W1, W2, rts_keys, dy, logits=None, seed=0):

@@ -151,3 +151,57 @@ def test_argument_errors_leave_outputs_untouched():
         B.moe_gate_route(s, logits, None, torch.empty(64, 4, device="cuda"), i32(64, 1),
                          torch.empty(64, 1, device="cuda"), i32(64, 1), i32(4), i32(4), i32(4, 16),
                          ws_small)
+
+
+@pytest.mark.parametrize("T,d,E,k,C,dtype,eps", [
+    (777, 136, 5, 2, 200, I.F32, 0.0),        # ragged T and d, E not a multiple of 4
+    (1000, 72, 7, 1, 130, I.F32, 0.0),
+    (1500, 264, 6, 2, 400, I.BF16, 0.0),
+    (2049, 320, 40, 1, 300, I.BF16, 0.0),     # two 32-expert blocks
+    (640, 128, 8, 2, 96, I.BF16, 0.05),       # with gate jitter
+    (4096, 1024, 32, 2, 512, I.BF16, 0.0),    # cfg3's row length
+])
+def test_dispatch_backward_fused_with_gate_projection_backward(T, d, E, k, C, dtype, eps):
+    """dx = (sum of the token's kept rows of dxd) + dlogits Wg^T in one call, on a
+    hand-made assignment: a third of the choices dropped, some tokens without any
+    kept choice, every kept choice in a distinct row of its expert."""
+    rng = np.random.default_rng(T + d)
+    expert_idx = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    slot = np.full((T, k), -1, np.int32)
+    fill = np.zeros(E, np.int64)
+    for t in range(T):
+        if rng.random() < 0.1:
+            continue                                   # token dropped by both experts
+        for j in range(k):
+            e = expert_idx[t, j]
+            if rng.random() < 0.75 and fill[e] < C:
+                slot[t, j] = fill[e]
+                fill[e] += 1
+    # rows in shuffled order inside each expert, so that slots are not monotone in t
+    for e in range(E):
+        perm = rng.permutation(C)
+        m = (expert_idx == e) & (slot >= 0)
+        slot[m] = perm[slot[m]]
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    dxd = rng.standard_normal((E, C, d)).astype(np.float32)
+    Wg = (rng.standard_normal((d, E)) * 0.5).astype(np.float32)
+    dl = (rng.standard_normal((T, E)) * 0.5).astype(np.float32)
+    if dtype == I.BF16:
+        x, dxd = I.round_to_bf16(x), I.round_to_bf16(dxd)
+    shape = B.make_shape(T, d, 4 * d, E, k, C, dtype, I.GELU)
+    ws = torch.empty(B.moe_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    dWg = torch.empty((d, E), dtype=torch.float32, device="cuda")
+    dx = G.to_dev(rng.standard_normal((T, d)).astype(np.float32), dtype)     # garbage: must be overwritten
+    print(f"[gpu] fused dispatch/gate backward T={T} d={d} E={E} k={k} eps={eps}", flush=True)
+    B.moe_dispatch_gate_logits_bwd(shape, G.to_dev(x, dtype), G.to_dev(Wg, I.F32), G.to_dev(dl, I.F32),
+                                   G.to_dev(dxd, dtype), G.to_dev(expert_idx, None), G.to_dev(slot, None),
+                                   eps, 11, dWg, dx, ws)
+    torch.cuda.synchronize()
+    noise = O.jitter_noise(T, d, eps, 11) if eps else 1.0
+    dWg_ref, dx_gate = O.gate_logits_bwd(x * noise, Wg, dl)
+    dx_ref = O.combine_fwd(dxd, expert_idx, slot) + dx_gate * noise
+    assert G.rel_l2(G.host(dWg), dWg_ref) <= 1e-5
+    assert G.rel_l2(G.host(dx), dx_ref) <= G.TOL[dtype]
+    none_kept = (slot < 0).all(axis=1)
+    assert none_kept.any()
+    assert G.rel_l2(G.host(dx)[none_kept], (dx_gate * noise)[none_kept]) <= G.TOL[dtype]
