@@ -553,8 +553,10 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                     aux[buf][q][it] = Vec4buf<T>::load(to.ax, out_off(mrow + i * 32 + q * 8 + it * RPI));
         };
         if constexpr (EPI == EPI_MUL) {
+            if (nk == 0) {
 #pragma unroll
-            for (int i = 0; i < AUXB; ++i) fetch_aux(i, i);
+                for (int i = 0; i < AUXB; ++i) fetch_aux(i, i);
+            }
         }
 
         f32x16_t acc[TM][TN];
@@ -588,6 +590,14 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                     wait_vmcnt_lgkm0<(NS - 2) * SM::LOADS>();
                     __builtin_amdgcn_s_barrier();
                     asm volatile("" ::: "memory");
+                    if constexpr (EPI == EPI_MUL) {
+                        // requested right after a wait, a whole slab period before the next one:
+                        // every wait of the loop is for all outstanding loads, these included
+                        if (kt == 0) {
+#pragma unroll
+                            for (int i = 0; i < AUXB; ++i) fetch_aux(i, i);
+                        }
+                    }
                     produce_prepare(stage);
                     const unsigned char* a_n = smem_raw + next * SM::STAGE;
                     // hand-laid schedule of the last step: per MFMA one slab request and one
