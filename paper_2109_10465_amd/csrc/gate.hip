@@ -236,8 +236,17 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
     constexpr int GRP = 4;                               // token pairs whose loads are in flight together (x2 buffers)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, h = lane >> 5;
-    const int i0 = blockIdx.x * GW_COLS, e0 = blockIdx.z * 32;
-    const int tbeg = blockIdx.y * tok_per_chunk;
+    // Workgroups are handed to the 8 XCDs round robin: the column blocks of one token
+    // chunk go to the same XCD, so that the pieces of a row of x are requested through
+    // one L2 (chunk index c, column block b from the linear workgroup number)
+    int bx = blockIdx.x, by = blockIdx.y;
+    if ((gridDim.y & 7) == 0) {
+        const int lin = blockIdx.x + gridDim.x * blockIdx.y;
+        bx = (lin >> 3) % gridDim.x;
+        by = (lin & 7) + 8 * (lin / (8 * gridDim.x));
+    }
+    const int i0 = bx * GW_COLS, e0 = blockIdx.z * 32;
+    const int tbeg = by * tok_per_chunk;
     const int tend = min(Tn, tbeg + tok_per_chunk);
     const int per_wave = tok_per_chunk / GW_WAVES;
     const int w_lo = tbeg + wave * per_wave, w_hi = min(tend, w_lo + per_wave);
@@ -251,6 +260,50 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
     for (int c = 0; c < 8; ++c)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[c][v] = 0.0f;
+    if constexpr (sizeof(T) == 2 && !JIT) {
+        // bf16 activations on the bf16 matrix pipe (32x32x16: a lane supplies 8 consecutive
+        // k = tokens).  A lane loads 8 columns x 8 tokens (one 16-byte load per token),
+        // transposes the 8x8 block in registers (one byte permute per packed pair) into the
+        // 8 operands "column 8r+c of tokens 8h..8h+7", and multiplies each with dlogits split
+        // exactly into three bf16 parts: 24 steps of 32 cycles per 16 tokens instead of 64 of 64.
+        auto fetch16 = [&](int t, u32x4_buf_t (&fx)[8], float (&fd)[8]) {
+#pragma unroll
+            for (int s_ = 0; s_ < 8; ++s_) {
+                const int tok = t + 8 * h + s_;
+                const bool ok = tok < w_hi;              // the next wave's tokens are not ours
+                fx[s_] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rs_x, ok && col_ok ? (uint32_t)(((tok - tbeg) * d + col) * sizeof(T)) : BUF_OOB, 0, 0);
+                fd[s_] = buf_load_f32(rs_d, ok && e_ok ? (uint32_t)(((tok - tbeg) * E + e0 + r) * 4) : BUF_OOB);
+            }
+        };
+        auto multiply16 = [&](const u32x4_buf_t (&fx)[8], const float (&fd)[8]) {
+            bf16x8_hw_t d_hi, d_mid, d_lo;
+            split3_bf16(fd, d_hi, d_mid, d_lo);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                u32x4_buf_t q;
+#pragma unroll
+                for (int w = 0; w < 4; ++w)   // tokens 2w (low half) and 2w+1 (high half) at column c
+                    q[w] = __builtin_amdgcn_perm(fx[2 * w + 1][c >> 1], fx[2 * w][c >> 1],
+                                                 (c & 1) ? 0x07060302u : 0x05040100u);
+                const bf16x8_hw_t xa = __builtin_bit_cast(bf16x8_hw_t, q);
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, d_lo, acc[c], 0, 0, 0);
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, d_mid, acc[c], 0, 0, 0);
+                acc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, d_hi, acc[c], 0, 0, 0);
+            }
+        };
+        // two register buffers: the loads of the next 16 tokens travel under this group's MFMAs
+        // (more requests in flight only queue up: the first data then arrives later)
+        u32x4_buf_t xa0[8], xa1[8];
+        float dl0[8], dl1[8];
+        fetch16(w_lo, xa0, dl0);
+        for (int t = w_lo; t < w_hi; t += 32) {
+            fetch16(t + 16, xa1, dl1);       // beyond w_hi: every lane reads zeros, harmless
+            multiply16(xa0, dl0);
+            fetch16(t + 32, xa0, dl0);
+            multiply16(xa1, dl1);
+        }
+    } else {
     // two register buffers: the loads of the next group travel under this group's MFMAs
     float a[2][GRP][8], b[2][GRP];
     auto fetch = [&](int t, float (&fa)[GRP][8], float (&fb)[GRP]) {
@@ -280,6 +333,7 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
         fetch(t + 4 * GRP, a[0], b[0]);
         multiply(t + 2 * GRP, a[1], b[1]);
     }
+    }
     // accumulator v of tile c, lane l: column i0 + 8*(8*(v/4) + 4*(l/32) + v%4) + c, expert e0 + l%32
 #pragma unroll
     for (int c = 0; c < 8; ++c)
@@ -289,12 +343,36 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
             gw_red[(wave * GW_COLS + 8 * m + c) * 32 + r] = acc[c][v];
         }
     __syncthreads();
-    for (int o = threadIdx.x; o < GW_COLS * 32; o += 64 * GW_WAVES) {
-        const int il = o >> 5, e = o & 31;
-        float sum = 0.0f;
+    // 4 experts per thread and pass; every LDS read of the loop is issued before the first add
+    constexpr int NPASS = GW_COLS * 32 / 4 / (64 * GW_WAVES);
+    float4 part[NPASS][GW_WAVES];
 #pragma unroll
-        for (int w = 0; w < GW_WAVES; ++w) sum += gw_red[(w * GW_COLS + il) * 32 + e];
-        if (i0 + il < d && e0 + e < E) partial[((size_t)blockIdx.y * d + i0 + il) * E + e0 + e] = sum;
+    for (int q = 0; q < NPASS; ++q)
+#pragma unroll
+        for (int w = 0; w < GW_WAVES; ++w)
+            part[q][w] = *reinterpret_cast<const float4*>(
+                &gw_red[(size_t)(w * GW_COLS) * 32 + (size_t)(q * 64 * GW_WAVES + threadIdx.x) * 4]);
+    const bool e_vec = (E & 3) == 0;
+#pragma unroll
+    for (int q = 0; q < NPASS; ++q) {
+        const int o = (q * 64 * GW_WAVES + threadIdx.x) * 4;
+        const int il = o >> 5, e = o & 31;
+        float4 sum = part[q][0];
+#pragma unroll
+        for (int w = 1; w < GW_WAVES; ++w) {   // in wave order: reproducible
+            sum.x += part[q][w].x; sum.y += part[q][w].y; sum.z += part[q][w].z; sum.w += part[q][w].w;
+        }
+        if (i0 + il < d) {
+            float* dst = partial + ((size_t)by * d + i0 + il) * E + e0 + e;
+            if (e_vec && e0 + e + 3 < E) {
+                *reinterpret_cast<float4*>(dst) = sum;
+            } else {
+                const float v4[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (e0 + e + j < E) dst[j] = v4[j];
+            }
+        }
     }
 }
 
