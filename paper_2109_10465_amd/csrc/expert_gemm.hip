@@ -504,9 +504,6 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
         for (int i = 0; i < SM::LOADS; ++i) produce_issue(i);
     };
 
-#ifdef MOE_GEMM_CLOCKDBG
-    const long long dbg_c0 = clock64(), dbg_w0 = wall_clock64();
-#endif
     // ---- consumer ---------------------------------------------------------------
     TileWalk<BM, BN> cw;
     cw.start(p, walk_lds);
@@ -696,12 +693,6 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
     // the zero-fill loads requested past the end of the stream target this
     // workgroup's LDS: wait for them before the workgroup retires
     wait_vmcnt<0>();
-#ifdef MOE_GEMM_CLOCKDBG
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        ((long long*)p.out0)[0] = clock64() - dbg_c0;
-        ((long long*)p.out0)[1] = wall_clock64() - dbg_w0;
-    }
-#endif
 }
 
 // Number of compute units (cached; the library keeps no other state).

@@ -1,16 +1,19 @@
 // Gate projection and the gate's backward (Sec. 3.2: one gate matrix column per
-// expert; Sec. 5.1: top-1 / top-2 gating).  All math in fp32; reductions run in
-// a fixed order so results are bit-reproducible.
+// expert; Sec. 5.1: top-1 / top-2 gating).  Results have fp32 accuracy: fp32
+// activations run on the fp32 matrix pipe; bf16 activations run on the bf16 pipe
+// with every fp32 operand split into bf16 parts whose products are exact in fp32.
+// Reductions run in a fixed order so results are bit-reproducible.
 #include "moe_common.h"
 
 // ---------------------------------------------------------------------------
-// logits[T,E] = x[T,d] * Wg[d,E] (+ bias)   on the fp32 matrix pipe
+// logits[T,E] = x[T,d] * Wg[d,E] (+ bias)   on the matrix pipe
 // Workgroup: 32 tokens x all experts, 8 waves that split the reduction over d.
 // v_mfma_f32_32x32x2_f32: lane (r = l%32, h = l/32) supplies A[token r][k] and
 // B[k][expert r] for ONE k per instruction.  The order of a reduction is free,
 // so a lane's 8 consecutive x values (one 16-byte load for bf16) serve 8
-// instructions: in a 16-deep block, instruction s uses k = 8h + s.  Wg (L2
-// resident) is read as 128-byte rows.  All loads of a group of blocks are in
+// instructions: in a 16-deep block, instruction s uses k = 8h + s.
+// v_mfma_f32_32x32x16_bf16 takes exactly those 8 values per lane in one step.
+// Wg (L2 resident) is read as 128-byte rows.  All loads of a group of blocks are in
 // flight before the first MFMA; other waves cover the latency.  The 8 partial
 // tiles are added in wave order through LDS, so the result is reproducible.
 // ---------------------------------------------------------------------------
@@ -198,7 +201,7 @@ extern "C" int moe_gate_bwd(const moe_shape* shape, const float* dgate_w, const 
 }
 
 // ---------------------------------------------------------------------------
-// dWg[d,E] = x^T dlogits   on the fp32 matrix pipe: partial sums over token
+// dWg[d,E] = x^T dlogits   on the matrix pipe: partial sums over token
 // chunks, then an ordered sum over the chunks.
 // Workgroup: 256 columns of d x 32 experts x one chunk of tokens, 4 waves that
 // split the chunk's tokens.  The reduction runs over tokens, two per MFMA (one
@@ -395,7 +398,7 @@ __global__ __launch_bounds__(256) void gate_dwg_reduce_kernel(int n, int nchunk,
 }
 
 // ---------------------------------------------------------------------------
-// dx[t,:] (+)= dlogits[t,:] * Wg^T   on the fp32 matrix pipe
+// dx[t,:] (+)= dlogits[t,:] * Wg^T   on the matrix pipe
 // Workgroup: 32 tokens, 4 waves; wave w takes the 64-column passes w, w+4, ...
 // of d (two 32x32 tiles, D[token][column]).  A = dlogits rows (token, all
 // experts), B = Wg rows (column i, all experts): both are contiguous along the
