@@ -254,11 +254,44 @@ def main():
     }
     if breakdown is not None:
         out["breakdown"] = breakdown
+    out["measured_peaks"] = measured_peaks(torch, B)
     if not args.no_cpu_baseline:
         del x, dy, W1, W2, layer, L
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w, d, forward_only=args.forward_only)
     print(json.dumps(out), flush=True)
+
+
+def measured_peaks(torch, B):
+    """What this machine sustains, for scale beside the published peaks the fractions are quoted against: a plain
+    device-to-device copy (read + write bytes) and a register-resident bf16 MFMA loop (random and all-equal
+    operands: the clock under matrix load depends on the data).  Outside the timed region; a failure here never
+    costs the benchmark line."""
+    try:
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e-3 / reps
+        src = torch.empty(1 << 27, dtype=torch.float32, device="cuda").normal_()      # 512 MiB
+        dst = torch.empty_like(src)
+        t_copy = timed(lambda: dst.copy_(src), 5)
+        del dst
+        n_wg = 4 * torch.cuda.get_device_properties(0).multi_processor_count         # 2 waves per SIMD
+        outb = torch.empty(n_wg * 256, dtype=torch.float32, device="cuda")
+        iters = 20000
+        flop = n_wg * 4 * iters * 8 * 32768.0
+        res = {"copy_TBps": 2 * src.numel() * 4 / t_copy / 1e12, "published": {"hbm_TBps": 8.0, "mfma_bf16_TFLOPs": 2500.0}}
+        for name, rnd in (("mfma_bf16_TFLOPs_random_operands", 1), ("mfma_bf16_TFLOPs_equal_operands", 0)):
+            res[name] = flop / timed(lambda: B.moe_microbench_mfma_bf16(n_wg, iters, rnd, outb), 3) / 1e12
+        return res
+    except Exception as exc:      # noqa: BLE001 - report, never fail the line
+        return {"error": repr(exc)}
 
 
 if __name__ == "__main__":

@@ -267,6 +267,15 @@ int moe_dispatch_gate_logits_bwd(const moe_shape* shape, const void* x, const fl
                                  const int32_t* slot, float jitter_eps, uint64_t seed, float* dWg,
                                  void* dx, void* ws, size_t ws_bytes, void* stream);
 
+/* Measurement aid, not a step of the layer (for benchmarks that print what the
+ * chip sustains beside the published peak): n_workgroups x 4 waves each issue
+ * iters x 8 independent v_mfma_f32_32x32x16_bf16 on register-resident operands
+ * (random_operands != 0: seeded pseudo-random values, else all-equal ones).
+ * Work = n_workgroups * 4 * iters * 8 * 32768 flop; the caller times it.
+ * out: n_workgroups * 256 floats, written once so that the loop is not dead code. */
+int moe_microbench_mfma_bf16(int32_t n_workgroups, int32_t iters, int32_t random_operands, float* out,
+                             void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,7 @@ EXPORTS = [
     "moe_gate_bwd", "moe_gate_logits_bwd", "moe_aux_loss", "moe_gate_bwd_aux",
     "moe_utilisation_accumulate", "moe_gate_route_grouped",
     "moe_gate_logits_jitter", "moe_gate_logits_bwd_jitter", "moe_expert_ffn_fwd_dropout",
-    "moe_dispatch_gate_logits_bwd",
+    "moe_dispatch_gate_logits_bwd", "moe_microbench_mfma_bf16",
 ]
 
 
@@ -72,6 +72,7 @@ def lib():
             "moe_gate_logits_bwd_jitter": [shp, vp, vp, vp, ctypes.c_float, ctypes.c_uint64, vp, vp, vp, sz, vp],
             "moe_expert_ffn_fwd_dropout": [shp] + [vp] * 4 + [ctypes.c_float, ctypes.c_uint64] + [vp] * 4,
             "moe_dispatch_gate_logits_bwd": [shp] + [vp] * 6 + [ctypes.c_float, ctypes.c_uint64, vp, vp, vp, sz, vp],
+            "moe_microbench_mfma_bf16": [i32, i32, i32, vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(L, name)
@@ -202,6 +203,11 @@ def moe_dispatch_gate_logits_bwd(shape, x, Wg, dlogits, dxd, expert_idx, slot, j
                                               float(jitter_eps), int(seed), _p(dWg), _p(dx), _p(ws),
                                               0 if ws is None else ws.numel() * ws.element_size(),
                                               _stream(stream)), "moe_dispatch_gate_logits_bwd")
+
+
+def moe_microbench_mfma_bf16(n_workgroups, iters, random_operands, out, stream=None):
+    _check(lib().moe_microbench_mfma_bf16(int(n_workgroups), int(iters), int(bool(random_operands)), _p(out),
+                                          _stream(stream)), "moe_microbench_mfma_bf16")
 
 
 def moe_expert_ffn_fwd_dropout(shape, xd, expert_count, W1, W2, drop_p, seed, h_saved, dact_saved, yd,

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmoe_hip.so")
-SOURCES = ["api.hip", "route.hip", "gate.hip", "aux_loss.hip", "permute.hip", "expert_gemm.hip"]
+SOURCES = ["api.hip", "route.hip", "gate.hip", "aux_loss.hip", "permute.hip", "expert_gemm.hip", "microbench.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 VALU forms are kept out of generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -205,3 +205,14 @@ def test_dispatch_backward_fused_with_gate_projection_backward(T, d, E, k, C, dt
     none_kept = (slot < 0).all(axis=1)
     assert none_kept.any()
     assert G.rel_l2(G.host(dx)[none_kept], (dx_gate * noise)[none_kept]) <= G.TOL[dtype]
+
+
+def test_mfma_rate_aid_counts_what_it_claims():
+    """The measurement aid's work formula (4 waves x iters x 8 MFMAs of 32x32x16 per workgroup) holds: with
+    operands 0.5 and 1.0 every accumulator element gains 16 * 0.5 per MFMA, and a lane sums 8 tiles x 16 elements."""
+    out = torch.zeros(3 * 256, dtype=torch.float32, device="cuda")
+    B.moe_microbench_mfma_bf16(3, 10, 0, out)
+    torch.cuda.synchronize()
+    assert torch.all(out == 8 * 16 * 8.0 * 10)
+    with pytest.raises(B.MoeError):
+        B.moe_microbench_mfma_bf16(0, 10, 0, out)
