@@ -24,6 +24,8 @@
 #define CHUNK 256       // tokens per histogram chunk (= per gate_topk / route_place workgroup)
 #define RANK_TILE 256   // candidates per route_rank workgroup
 #define RANK_PARTS 4    // threads per candidate: each counts over a quarter of every staged tile
+#define RANK_PAIR_TILES 4   // segments longer than this many tiles are ranked through key buckets
+#define RANK_BUCKETS 1024   // = threads of a route_rank workgroup
 
 struct RouteWs {
     int32_t* hist;        // [nchunk][k*E] candidates per chunk and segment
@@ -398,7 +400,71 @@ __global__ __launch_bounds__(RANK_TILE * RANK_PARTS) void route_rank_kernel(
     const int tok = (valid && part == 0) ? seg_tok[p] : 0;
     const int row0 = goff[(size_t)grp * E + e];             // earlier groups' rows come first
     int cnt = p - s0;  // position priority: candidates are stored in token order
-    if (has_keys) {
+    const int n_seg = s1 - s0;
+    if (has_keys && n_seg > RANK_PAIR_TILES * RANK_TILE) {
+        // Long segment (skewed routing): counting every pair costs n per candidate.  Instead
+        // the workgroup buckets the segment's keys by value (any monotone bucket function keeps
+        // the result exact): candidates in higher buckets precede, and only the keys that fall
+        // into the bucket of one of the tile's own candidates are compared with it.  Three
+        // passes over the segment's keys (L2), each thread a strided share.
+        static_assert(RANK_BUCKETS == NT, "one bucket per thread");
+        __shared__ int s_hist[RANK_BUCKETS];      // keys per bucket, then inclusive prefix sums
+        __shared__ int s_head[RANK_BUCKETS];      // list of the tile's own candidates per bucket
+        __shared__ int s_next[RANK_TILE];
+        __shared__ float s_mine[RANK_TILE];
+        __shared__ int s_prec[RANK_TILE];         // same-bucket candidates that precede
+        __shared__ float s_lo[NT / 64], s_hi[NT / 64];
+        __shared__ int s_wtot[NT / 64];
+        const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+        float lo = INFINITY, hi = -INFINITY;
+        for (int i = threadIdx.x; i < n_seg; i += NT) {
+            const float kq = seg_key[s0 + i];
+            lo = fminf(lo, kq);
+            hi = fmaxf(hi, kq);
+        }
+        lo = -wave_max(-lo);
+        hi = wave_max(hi);
+        if (lane == 0) { s_lo[wv] = lo; s_hi[wv] = hi; }
+        s_hist[threadIdx.x] = 0;
+        s_head[threadIdx.x] = -1;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < NT / 64; ++w) { lo = fminf(lo, s_lo[w]); hi = fmaxf(hi, s_hi[w]); }
+        const float span = hi - lo;
+        const float scale = (span > 0.0f && span < INFINITY) ? (float)RANK_BUCKETS / span : 0.0f;
+        // monotone in the key: subtraction, a non-negative factor, the clamp and the truncation all are
+        // (scale 0 - all keys equal, or a span beyond fp32 - puts everything into bucket 0: still exact)
+        auto bucket = [&](float kq) {
+            return scale == 0.0f ? 0 : (int)fminf((kq - lo) * scale, (float)(RANK_BUCKETS - 1));
+        };
+        const float mine = (valid && part == 0) ? seg_key[p] : 0.0f;
+        const int my_b = bucket(mine);
+        if (valid && part == 0) {
+            s_mine[tid] = mine;
+            s_prec[tid] = 0;
+            s_next[tid] = atomicExch(&s_head[my_b], tid);
+        }
+        for (int i = threadIdx.x; i < n_seg; i += NT) atomicAdd(&s_hist[bucket(seg_key[s0 + i])], 1);
+        __syncthreads();
+        {   // inclusive prefix sums of the bucket counts: wave scan, then the earlier waves' totals
+            const int incl = wave_incl_scan(s_hist[threadIdx.x], lane);
+            if (lane == 63) s_wtot[wv] = incl;
+            __syncthreads();
+            int before = 0;
+            for (int w = 0; w < wv; ++w) before += s_wtot[w];
+            s_hist[threadIdx.x] = incl + before;
+        }
+        for (int i = threadIdx.x; i < n_seg; i += NT) {
+            const int q = s0 + i;
+            const float kq = seg_key[q];
+            for (int c = s_head[bucket(kq)]; c >= 0; c = s_next[c]) {
+                const float mc = s_mine[c];
+                if (kq > mc || (kq == mc && q < own0 + c)) atomicAdd(&s_prec[c], 1);   // equal keys: token order
+            }
+        }
+        __syncthreads();
+        if (valid && part == 0) cnt = (n_seg - s_hist[my_b]) + s_prec[tid];
+    } else if (has_keys) {
         const float mine = valid ? seg_key[p] : 0.0f;
         cnt = 0;
         float nxt = (part == 0 && s0 + tid < s1) ? seg_key[s0 + tid] : -INFINITY;

@@ -216,3 +216,41 @@ def test_mfma_rate_aid_counts_what_it_claims():
     assert torch.all(out == 8 * 16 * 8.0 * 10)
     with pytest.raises(B.MoeError):
         B.moe_microbench_mfma_bf16(0, 10, 0, out)
+
+
+@pytest.mark.parametrize("case", ["ties16", "all_equal", "wide_range", "one_expert"])
+def test_long_segments_rank_through_key_buckets(case):
+    """Segments of thousands of candidates (skewed routing) take the bucketed ranking path: same slots as the
+    oracle's pairwise definition, with massive key ties, identical keys, keys spanning many magnitudes and both
+    signs, and every token on one expert."""
+    rng = np.random.default_rng(17)
+    T, E, k = 12288, 3, 2
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    keys = rng.random(T).astype(np.float32)
+    if case == "ties16":
+        keys = np.floor(keys * 16).astype(np.float32) / 16
+    elif case == "all_equal":
+        keys[:] = 0.25
+    elif case == "wide_range":
+        keys = (np.sign(rng.standard_normal(T)) * np.exp(rng.uniform(-60, 60, T))).astype(np.float32)
+        keys[::7] = 0.0
+    elif case == "one_expert":
+        k = 1
+        logits[:, 1] += 50.0
+    C = 3000
+    shape = B.make_shape(T, 64, 128, E, k, C, I.F32, I.RELU)
+    ws = torch.empty(B.moe_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    i32 = lambda *s: torch.empty(s, dtype=torch.int32, device="cuda")
+    probs = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    gate_w = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    eidx, slot, cnt, dem, src = i32(T, k), i32(T, k), i32(E), i32(E), i32(E, C)
+    print(f"[gpu] long segments, case {case}", flush=True)
+    B.moe_gate_route(shape, G.to_dev(logits, I.F32), G.to_dev(keys, I.F32), probs, eidx, gate_w, slot, cnt, dem, src, ws)
+    torch.cuda.synchronize()
+    ref_idx = O.top_k(logits, k)
+    ref = dict(zip(("slot", "expert_count", "expert_demand", "slot_src"), O.route(ref_idx, keys, E, C)))
+    assert np.array_equal(G.host(eidx), ref_idx)
+    for name, got in (("slot", slot), ("expert_count", cnt), ("expert_demand", dem), ("slot_src", src)):
+        assert np.array_equal(G.host(got), ref[name]), name
+    assert ref["expert_demand"].max() > 4 * 256          # the bucketed path was taken
+    assert (ref["slot"] < 0).any()                       # and capacity dropped some candidates
