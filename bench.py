@@ -282,7 +282,7 @@ def measured_peaks(torch, B):
         dst = torch.empty_like(src)
         t_copy = timed(lambda: dst.copy_(src), 5)
         del dst
-        n_wg = 4 * torch.cuda.get_device_properties(0).multi_processor_count         # 2 waves per SIMD
+        n_wg = 4 * torch.cuda.get_device_properties(0).multi_processor_count         # 4 waves per SIMD
         outb = torch.empty(n_wg * 256, dtype=torch.float32, device="cuda")
         iters = 20000
         flop = n_wg * 4 * iters * 8 * 32768.0
