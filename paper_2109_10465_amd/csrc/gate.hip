@@ -35,45 +35,53 @@ __device__ __forceinline__ void load8<float>(__amdgpu_buffer_rsrc_t rs, uint32_t
     for (int i = 0; i < 4; ++i) { v[i] = lo[i]; v[4 + i] = hi[i]; }
 }
 
-template <typename T, int NB, bool JIT>   // JIT: gate jitter on (a separate instance keeps the plain one lean)
+// TT = 32-token tiles per workgroup: with more than 32 experts every workgroup reads all of
+// Wg (E * d * 4 bytes, from L2) once, so two token tiles share each of its fragments.
+template <typename T, int NB, bool JIT, int TT>   // JIT: gate jitter on (a separate instance keeps the plain one lean)
 __global__ __launch_bounds__(64 * GLM_KSPLIT, NB == 1 ? 4 : 2) void gate_logits_kernel(
     int Tn, int d, int E, const T* __restrict__ x, const float* __restrict__ Wg,
     const float* __restrict__ bias, float* __restrict__ logits, float jitter_eps, uint64_t seed) {
-    constexpr int GRP = NB <= 2 ? 8 : 4;   // 16-deep blocks whose loads are in flight together
+    constexpr int GRP = NB <= 2 && TT == 1 ? 8 : 4;   // 16-deep blocks whose loads are in flight together
     __shared__ float red[GLM_KSPLIT][32][33];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, h = lane >> 5;
-    const int t0 = blockIdx.x * 32;
-    const int rows_here = min(32, Tn - t0);
+    const int t0 = blockIdx.x * 32 * TT;
+    const int rows_here = min(32 * TT, Tn - t0);
     const __amdgpu_buffer_rsrc_t rs_x = buf_rsrc(x + (size_t)t0 * d, (size_t)rows_here * d * sizeof(T));
     const __amdgpu_buffer_rsrc_t rs_w = buf_rsrc(Wg, (size_t)d * E * 4);
     const int nblk = (d + 15) / 16;
     const int per_wave = (nblk + GLM_KSPLIT - 1) / GLM_KSPLIT;
     const int b_lo = wave * per_wave, b_hi = min(nblk, b_lo + per_wave);
-    glm_f32x16 acc[NB];
+    glm_f32x16 acc[TT][NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.0f;
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tt][nb][v] = 0.0f;
     // bf16 activations (no jitter): x goes to the bf16 matrix pipe as loaded and Wg as
     // three bf16 parts that add up to it exactly, so the fp32 result is kept at a
     // fraction of the fp32 pipe's time (one 32x32x16 step per part instead of eight 32x32x2)
     constexpr bool SPLIT = sizeof(T) == 2 && !JIT;
     for (int b0 = b_lo; b0 < b_hi; b0 += GRP) {
-        float a[SPLIT ? 1 : GRP][8];
-        u32x4_buf_t araw[SPLIT ? GRP : 1];
+        float a[SPLIT ? 1 : TT][SPLIT ? 1 : GRP][8];
+        u32x4_buf_t araw[SPLIT ? TT : 1][SPLIT ? GRP : 1];
 #pragma unroll
-        for (int u = 0; u < GRP; ++u) {
-            const int k = (b0 + u) * 16 + 8 * h;
-            const bool ok = b0 + u < b_hi && k < d;     // rows beyond T fall outside rs_x
-            const uint32_t off = ok ? (uint32_t)((r * d + k) * sizeof(T)) : BUF_OOB;
-            if constexpr (SPLIT) araw[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, off, 0, 0);
-            else load8<T>(rs_x, off, a[u]);
-        }
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int u = 0; u < GRP; ++u) {
+                const int k = (b0 + u) * 16 + 8 * h;
+                const bool ok = b0 + u < b_hi && k < d;     // rows beyond T fall outside rs_x
+                const uint32_t off = ok ? (uint32_t)(((tt * 32 + r) * d + k) * sizeof(T)) : BUF_OOB;
+                if constexpr (SPLIT) araw[tt][u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, off, 0, 0);
+                else load8<T>(rs_x, off, a[tt][u]);
+            }
         if constexpr (JIT) {   // the gate sees x * noise
 #pragma unroll
-            for (int u = 0; u < GRP; ++u)
-                jitter_scale<8>(a[u], (size_t)(t0 + r) * d + (b0 + u) * 16 + 8 * h, jitter_eps, seed);
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int u = 0; u < GRP; ++u)
+                    jitter_scale<8>(a[tt][u], (size_t)(t0 + tt * 32 + r) * d + (b0 + u) * 16 + 8 * h, jitter_eps, seed);
         }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
@@ -92,45 +100,57 @@ __global__ __launch_bounds__(64 * GLM_KSPLIT, NB == 1 ? 4 : 2) void gate_logits_
                 if constexpr (SPLIT) {
                     bf16x8_hw_t w_hi, w_mid, w_lo;
                     split3_bf16(bw[u], w_hi, w_mid, w_lo);
-                    const bf16x8_hw_t xa = __builtin_bit_cast(bf16x8_hw_t, araw[u]);
-                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_lo, acc[nb], 0, 0, 0);
-                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_mid, acc[nb], 0, 0, 0);
-                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_hi, acc[nb], 0, 0, 0);
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        const bf16x8_hw_t xa = __builtin_bit_cast(bf16x8_hw_t, araw[tt][u]);
+                        acc[tt][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_lo, acc[tt][nb], 0, 0, 0);
+                        acc[tt][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_mid, acc[tt][nb], 0, 0, 0);
+                        acc[tt][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa, w_hi, acc[tt][nb], 0, 0, 0);
+                    }
                 } else {
 #pragma unroll
-                    for (int s_ = 0; s_ < 8; ++s_)
-                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u][s_], bw[u][s_], acc[nb], 0, 0, 0);
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int s_ = 0; s_ < 8; ++s_)
+                            acc[tt][nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[tt][u][s_], bw[u][s_], acc[tt][nb], 0, 0, 0);
                 }
             }
         }
     }
     // accumulator element v of lane l: expert column l%32, token row 8*(v/4) + 4*(l/32) + v%4
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-        if (nb) __syncthreads();
+    for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) red[wave][8 * (v >> 2) + 4 * h + (v & 3)][r] = acc[nb][v];
-        __syncthreads();
+        for (int nb = 0; nb < NB; ++nb) {
+            if (tt + nb) __syncthreads();
 #pragma unroll
-        for (int o = threadIdx.x; o < 32 * 32; o += 64 * GLM_KSPLIT) {
-            const int m = o >> 5, n = o & 31, e = nb * 32 + n;
-            float sum = 0.0f;
+            for (int v = 0; v < 16; ++v) red[wave][8 * (v >> 2) + 4 * h + (v & 3)][r] = acc[tt][nb][v];
+            __syncthreads();
 #pragma unroll
-            for (int w = 0; w < GLM_KSPLIT; ++w) sum += red[w][m][n];
-            if (m < rows_here && e < E) logits[(size_t)(t0 + m) * E + e] = sum + (bias ? bias[e] : 0.0f);
+            for (int o = threadIdx.x; o < 32 * 32; o += 64 * GLM_KSPLIT) {
+                const int m = tt * 32 + (o >> 5), n = o & 31, e = nb * 32 + n;
+                float sum = 0.0f;
+#pragma unroll
+                for (int w = 0; w < GLM_KSPLIT; ++w) sum += red[w][o >> 5][n];
+                if (m < rows_here && e < E) logits[(size_t)(t0 + m) * E + e] = sum + (bias ? bias[e] : 0.0f);
+            }
         }
-    }
 }
 
 template <typename T>
 static void launch_gate_logits(const moe_shape* s, const void* x, const float* Wg, const float* bias,
                                float* logits, float eps, uint64_t seed, hipStream_t st) {
-    const int grid = ceil_div(s->T, 32);
-#define GLM(NB, JIT) gate_logits_kernel<T, NB, JIT><<<grid, 64 * GLM_KSPLIT, 0, st>>>(s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits, eps, seed)
-#define GLME(JIT) do { if (s->E <= 32) GLM(1, JIT); else if (s->E <= 64) GLM(2, JIT); \
-                       else if (s->E <= 128) GLM(4, JIT); else GLM(8, JIT); } while (0)
-    if (eps != 0.0f) GLME(true); else GLME(false);
-#undef GLME
+    // two token tiles per workgroup on the bf16 matrix path with more than 32 experts
+#define GLM(NB, JIT, TT) gate_logits_kernel<T, NB, JIT, TT><<<ceil_div(s->T, 32 * TT), 64 * GLM_KSPLIT, 0, st>>>( \
+    s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits, eps, seed)
+    constexpr int TT2 = sizeof(T) == 2 ? 2 : 1;
+    if (eps != 0.0f) {
+        if (s->E <= 32) GLM(1, true, 1); else if (s->E <= 64) GLM(2, true, 1);
+        else if (s->E <= 128) GLM(4, true, 1); else GLM(8, true, 1);
+    } else {
+        if (s->E <= 32) GLM(1, false, 1); else if (s->E <= 64) GLM(2, false, TT2);
+        else if (s->E <= 128) GLM(4, false, TT2); else GLM(8, false, 1);
+    }
 #undef GLM
 }
 
@@ -159,33 +179,47 @@ extern "C" int moe_gate_logits_jitter(const moe_shape* shape, const void* x, con
 // ---------------------------------------------------------------------------
 // dlogits from dgate_w (derivative of the gate weights and the softmax)
 // ---------------------------------------------------------------------------
+template <int V>   // V consecutive experts of one token per thread (V = 4 needs E % 4 == 0)
 __global__ __launch_bounds__(256) void gate_bwd_kernel(
     int Tn, int E, int k, const float* __restrict__ dgate_w, const float* __restrict__ probs,
     const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ slot,
     float* __restrict__ dlogits) {
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t idx = ((size_t)blockIdx.x * 256 + threadIdx.x) * V;
     if (idx >= (size_t)Tn * E) return;
     const int t = (int)(idx / E), e = (int)(idx - (size_t)t * E);
     const float* pr = probs + (size_t)t * E;
-    float dp_e = 0.0f, sum = 0.0f;
-    if (k == 1) {
-        const int e0 = expert_idx[t];
-        const float dg0 = slot[t] >= 0 ? dgate_w[t] : 0.0f;
-        sum = pr[e0] * dg0;
-        if (e == e0) dp_e = dg0;
+    float pe[V];
+    if constexpr (V == 4) {
+        const float4 q = *reinterpret_cast<const float4*>(pr + e);
+        pe[0] = q.x; pe[1] = q.y; pe[2] = q.z; pe[3] = q.w;
     } else {
-        const int e0 = expert_idx[2 * t], e1 = expert_idx[2 * t + 1];
+        pe[0] = pr[e];
+    }
+    float dp0 = 0.0f, dp1 = 0.0f, sum = 0.0f;
+    int e0, e1 = -1;
+    if (k == 1) {
+        e0 = expert_idx[t];
+        dp0 = slot[t] >= 0 ? dgate_w[t] : 0.0f;
+        sum = pr[e0] * dp0;
+    } else {
+        e0 = expert_idx[2 * t];
+        e1 = expert_idx[2 * t + 1];
         const float dg0 = slot[2 * t] >= 0 ? dgate_w[2 * t] : 0.0f;
         const float dg1 = slot[2 * t + 1] >= 0 ? dgate_w[2 * t + 1] : 0.0f;
         const float p0 = pr[e0], p1 = pr[e1];
         const float S = p0 + p1;
-        const float dp0 = p1 * (dg0 - dg1) / (S * S);
-        const float dp1 = p0 * (dg1 - dg0) / (S * S);
+        dp0 = p1 * (dg0 - dg1) / (S * S);
+        dp1 = p0 * (dg1 - dg0) / (S * S);
         sum = p0 * dp0 + p1 * dp1;
-        if (e == e0) dp_e = dp0;
-        if (e == e1) dp_e = dp1;
     }
-    dlogits[idx] = pr[e] * (dp_e - sum);
+    float out[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        const float dp_e = e + i == e0 ? dp0 : (e + i == e1 ? dp1 : 0.0f);
+        out[i] = pe[i] * (dp_e - sum);
+    }
+    if constexpr (V == 4) *reinterpret_cast<float4*>(dlogits + idx) = make_float4(out[0], out[1], out[2], out[3]);
+    else dlogits[idx] = out[0];
 }
 
 extern "C" int moe_gate_bwd(const moe_shape* shape, const float* dgate_w, const float* probs,
@@ -195,8 +229,12 @@ extern "C" int moe_gate_bwd(const moe_shape* shape, const float* dgate_w, const 
     if (rc) return rc;
     if (!dgate_w || !probs || !expert_idx || !slot || !dlogits) return MOE_ERR_NULL;
     const size_t n = (size_t)shape->T * shape->E;
-    gate_bwd_kernel<<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
-        shape->T, shape->E, shape->k, dgate_w, probs, expert_idx, slot, dlogits);
+    if (shape->E % 4 == 0)
+        gate_bwd_kernel<4><<<(unsigned)((n / 4 + 255) / 256), 256, 0, (hipStream_t)stream>>>(
+            shape->T, shape->E, shape->k, dgate_w, probs, expert_idx, slot, dlogits);
+    else
+        gate_bwd_kernel<1><<<(unsigned)((n + 255) / 256), 256, 0, (hipStream_t)stream>>>(
+            shape->T, shape->E, shape->k, dgate_w, probs, expert_idx, slot, dlogits);
     return launch_status();
 }
 
