@@ -120,3 +120,19 @@ class MoELayer:
     def step(self, x, Wg, bias, W1, W2, rts_keys, dy, logits=None, seed=0):
         self.forward(x, Wg, bias, W1, W2, rts_keys, logits, seed)
         return self.backward(dy)
+
+    def capture_step(self, x, Wg, bias, W1, W2, rts_keys, dy, seed=0):
+        """Records one forward+backward step into a HIP graph and returns it (`.replay()` runs the step again on
+        the same tensors: refill x, dy, the weights and the keys in place between replays).  The library
+        allocates nothing and clears nothing with memset, so every call of the step is a plain kernel node.
+        Replay takes the host out of the loop; the device time is the same as eager (measured: the chain of
+        dependent kernels, not their launch, sets the time of a step even for a 256-token layer).
+        The seed of the step's noise draws is a host value and is recorded with the graph."""
+        if self.forward_only:
+            raise B.MoeError("this layer was built forward-only")
+        self.step(x, Wg, bias, W1, W2, rts_keys, dy, seed=seed)       # first use of every kernel happens eagerly
+        torch.cuda.synchronize(self.device)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step(x, Wg, bias, W1, W2, rts_keys, dy, seed=seed)
+        return graph
