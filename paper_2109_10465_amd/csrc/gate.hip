@@ -277,16 +277,8 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
     constexpr int GRP = 4;                               // token pairs whose loads are in flight together (x2 buffers)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, h = lane >> 5;
-    // Workgroups are handed to the 8 XCDs round robin: the column blocks of one token
-    // chunk go to the same XCD, so that the pieces of a row of x are requested through
-    // one L2 (chunk index c, column block b from the linear workgroup number)
-    int bx = blockIdx.x, by = blockIdx.y;
-    if ((gridDim.y & 7) == 0) {
-        const int lin = blockIdx.x + gridDim.x * blockIdx.y;
-        bx = (lin >> 3) % gridDim.x;
-        by = (lin & 7) + 8 * (lin / (8 * gridDim.x));
-    }
-    const int i0 = bx * GW_COLS, e0 = blockIdx.z * 32;
+    const int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    const int i0 = bx * GW_COLS, e0 = bz * 32;
     const int tbeg = by * tok_per_chunk;
     const int tend = min(Tn, tbeg + tok_per_chunk);
     const int per_wave = tok_per_chunk / GW_WAVES;
