@@ -46,8 +46,8 @@ def cpu_baseline(w, d, budget_flops=2.0e12, forward_only=False):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--aux-coef", type=float, default=0.0,
                     help="weight of the balancing auxiliary loss (Sec. 5.1 uses 0.01); 0 = the plain hot path")
@@ -142,9 +142,11 @@ def main():
     timed = [n for n, _ in calls if n in gemm_calls or n in hbm_calls]
     ev = [{n: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for n in timed}
           for _ in range(args.steps)]
+    step_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
+        step_ev[i][0].record()
         for name, fn in calls:
             if name in ev[i]:
                 ev[i][name][0].record()
@@ -152,9 +154,11 @@ def main():
                 ev[i][name][1].record()
             else:
                 fn()
+        step_ev[i][1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
+    step_ms = sorted(a.elapsed_time(b) for a, b in step_ev)     # per step, HIP events on the same stream
     call_ms = {n: sum(e[n][0].elapsed_time(e[n][1]) for e in ev) / args.steps for n in timed}
     gemm_ms = sum(v for n, v in call_ms.items() if n in gemm_calls)
 
@@ -233,6 +237,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "ms_per_step_median": step_ms[len(step_ms) // 2],
+        "ms_per_step_min": step_ms[0],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
