@@ -138,7 +138,7 @@ def main():
     # timed region: exactly K steps; HIP events (torch's current stream is the
     # stream the kernels are launched on) bracket the expert-GEMM calls
     # and, for the HBM-bound steps the metric also names, the route / dispatch / combine calls
-    hbm_calls = ("gate_route", "dispatch", "combine_fwd", "combine_bwd", "dispatch_gate_logits_bwd")
+    hbm_calls = ("gate_logits", "gate_route", "dispatch", "combine_fwd", "combine_bwd", "dispatch_gate_logits_bwd")
     timed = [n for n, _ in calls if n in gemm_calls or n in hbm_calls]
     ev = [{n: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for n in timed}
           for _ in range(args.steps)]
@@ -198,6 +198,13 @@ def main():
     hbm = {n: {"us": call_ms[n] * 1e3, "GBps": alg[n] / (call_ms[n] * 1e-3) / 1e9,
                "frac_of_8TBps": alg[n] / (call_ms[n] * 1e-3) / PEAK_HBM}
            for n in hbm_calls if n in call_ms}
+
+    if "gate_logits" in hbm and "gate_route" in hbm:
+        # the gate projection, softmax/top-k and the capacity rank together: the only part of "route" with real
+        # HBM traffic is the projection's read of x; the rank itself is integer work on data that lives in L2
+        us = hbm["gate_logits"]["us"] + hbm["gate_route"]["us"]
+        by = alg["gate_logits"] + alg["gate_route"]
+        hbm["route_a0_a3"] = {"us": us, "GBps": by / (us * 1e-6) / 1e9, "frac_of_8TBps": by / (us * 1e-6) / PEAK_HBM}
 
     breakdown = None
     if args.breakdown:
