@@ -151,6 +151,20 @@ def test_argument_errors_leave_outputs_untouched():
         B.moe_gate_route(s, logits, None, torch.empty(64, 4, device="cuda"), i32(64, 1),
                          torch.empty(64, 1, device="cuda"), i32(64, 1), i32(4), i32(4), i32(4, 16),
                          ws_small)
+    # the fused backward call: missing dxd / slot / dx, bad jitter range, short workspace
+    ws = torch.empty(B.moe_workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    dxd = torch.zeros(4, 16, 16, device="cuda")
+    dWg, dx = torch.full((16, 4), 7.0, device="cuda"), torch.full((64, 16), 7.0, device="cuda")
+    eidx, slot = torch.zeros(64, 1, dtype=torch.int32, device="cuda"), torch.zeros(64, 1, dtype=torch.int32, device="cuda")
+    for args, what in (((s, x, Wg, logits, None, eidx, slot, 0.0, 0, dWg, dx, ws), "NULL"),
+                       ((s, x, Wg, logits, dxd, eidx, None, 0.0, 0, dWg, dx, ws), "NULL"),
+                       ((s, x, Wg, logits, dxd, eidx, slot, 0.0, 0, dWg, None, ws), "NULL"),
+                       ((s, x, Wg, logits, dxd, eidx, slot, 1.5, 0, dWg, dx, ws), "shape"),
+                       ((s, x, Wg, logits, dxd, eidx, slot, 0.0, 0, dWg, dx, ws_small[:64]), "workspace")):
+        with pytest.raises(B.MoeError, match=what):
+            B.moe_dispatch_gate_logits_bwd(*args)
+    torch.cuda.synchronize()
+    assert torch.all(dWg == 7.0) and torch.all(dx == 7.0)
 
 
 @pytest.mark.parametrize("T,d,E,k,C,dtype,eps", [
