@@ -76,3 +76,28 @@ def test_grouped_argument_errors():
     shape2 = B.make_shape(1024, 16, 16, 4, 1, 66, B.F32, 0)     # capacity not a multiple of 4
     with pytest.raises(B.MoeError):
         B.moe_gate_route_grouped(shape2, 4, *args[:8], t((4, 66), torch.int32), ws)
+
+
+def test_grouped_selection_with_long_segments():
+    """Groups whose (expert, choice) segments hold thousands of candidates: the bucketed ranking path with
+    per-group segment tables and per-group row offsets, routing integers in full against the oracle."""
+    rng = np.random.default_rng(23)
+    T, E, k, groups, C = 16384, 3, 2, 2, 4096
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    keys = (np.floor(rng.random(T) * 64) / 64).astype(np.float32)          # many equal keys
+    eidx = O.top_k(logits, k)
+    slot, count, demand, slot_src = O.route_grouped(eidx, keys, E, C, groups)
+    assert demand.max() // groups > 4 * 256 and (slot < 0).any()
+    shape = B.make_shape(T, 64, 128, E, k, C, I.F32, I.RELU)
+    ws = torch.empty(B.moe_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    i32, f32 = torch.int32, torch.float32
+    mk = lambda shp, dt: torch.empty(shp, dtype=dt, device="cuda")
+    probs, ei, gw, sl = mk((T, E), f32), mk((T, k), i32), mk((T, k), f32), mk((T, k), i32)
+    cnt, dem, src = mk((E,), i32), mk((E,), i32), mk((E, C), i32)
+    print("[gpu] grouped routing, long segments", flush=True)
+    B.moe_gate_route_grouped(shape, groups, G.to_dev(logits, I.F32), G.to_dev(keys, I.F32), probs, ei, gw, sl,
+                             cnt, dem, src, ws)
+    torch.cuda.synchronize()
+    for got, want, n in ((ei, eidx, "expert_idx"), (sl, slot, "slot"), (cnt, count, "expert_count"),
+                         (dem, demand, "expert_demand"), (src, slot_src, "slot_src")):
+        assert np.array_equal(G.host(got), want), n
