@@ -166,21 +166,37 @@ def main():
     n_gemm = 2 if args.forward_only else 6
     flops = 2.0 * n_gemm * M * w.d_model * w.d_ff             # grouped GEMMs of 2*M*d*f each
     peak = PEAK_BF16_MFMA if w.dtype == I.BF16 else PEAK_F32_MFMA
-    achieved = flops / (gemm_ms * 1e-3)
-    traffic = None
+    sb = 2 if w.dtype == I.BF16 else 4
+    # algorithmic HBM bytes of the expert FFN (what the method must move on kept rows, each tensor once):
+    # forward: xd, yd, the saved activation, W1, W2; backward adds dyd, xd, the saved activation, W1, W2 read and
+    # dxd and the fp32 dW1, dW2 written
+    ffn_bytes = M * (2 * w.d_model + w.d_ff) * sb + 2 * w.E * w.d_model * w.d_ff * sb
+    if not args.forward_only:
+        ffn_bytes += M * (3 * w.d_model + w.d_ff) * sb + 2 * w.E * w.d_model * w.d_ff * sb + 8 * w.E * w.d_model * w.d_ff
+    t_mfma, t_hbm = flops / peak, ffn_bytes / PEAK_HBM        # the two floors of the GEMM phase
+    gemm_s = gemm_ms * 1e-3
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", f"grouped_gemm_{w.name}_hbm_traffic.txt")
     if os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch"):
                 traffic = float(line.split("=")[1])
-    roofline = {"bound": "mfma", "kernel": f"grouped_gemm_kernel ({n_gemm} launches per step)",
-                "achieved": achieved / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
-                "frac": achieved / peak, "traffic": traffic,
-                "flops_per_launch": flops / n_gemm, "avg_launch_ms": gemm_ms / n_gemm,
-                "kept_assignments": M}
+            if line.startswith("measured_at_commit"):
+                traffic_source = f"profiles/{os.path.basename(tpath)} (rocprofv3 counters, kernels of commit {line.split('=')[1].strip()})"
+    if t_mfma >= t_hbm:
+        roofline = {"bound": "mfma", "achieved": flops / gemm_s / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
+                    "frac": flops / gemm_s / peak}
+    else:       # few rows per expert: weight and weight-gradient traffic, not the matrix pipe, bounds the FFN
+        roofline = {"bound": "hbm", "achieved": ffn_bytes / gemm_s / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                    "frac": ffn_bytes / gemm_s / PEAK_HBM}
+    roofline.update({"kernel": f"grouped_gemm_kernel ({n_gemm} launches per step)", "traffic": traffic,
+                     "traffic_source": traffic_source,
+                     "flops_per_launch": flops / n_gemm, "algorithmic_bytes_per_launch": ffn_bytes / n_gemm,
+                     "avg_launch_ms": gemm_ms / n_gemm, "kept_assignments": M,
+                     "floor_ms": {"mfma": t_mfma * 1e3, "hbm": t_hbm * 1e3},
+                     "frac_of_mfma_peak": flops / gemm_s / peak, "frac_of_hbm_peak": ffn_bytes / gemm_s / PEAK_HBM})
 
     # algorithmic HBM bytes per call (each tensor once; gathered rows counted per use)
-    sb = 2 if w.dtype == I.BF16 else 4
     Tn, dm, E, k, C = w.T, w.d_model, w.E, w.k, w.capacity
     kept_tok = int((L.slot >= 0).any(dim=1).sum().item())
     alg = {
@@ -257,22 +273,43 @@ def main():
                    "drop_p": args.drop_p,
                    "mode": "forward-only (evaluation)" if args.forward_only else "forward+backward (training)",
                    "kept_assignments": M,
+                   "tokens_fully_dropped": int((L.slot < 0).all(dim=1).sum().item()),
+                   "gate_skew": gate_skew(w, d["bias"]),
                    "expert_demand_max": int(L.expert_demand.max().item()),
-                   "expert_demand_min": int(L.expert_demand.min().item())},
+                   "expert_demand_min": int(L.expert_demand.min().item()),
+                   "expert_demand": [int(v) for v in L.expert_demand.cpu().tolist()]},
         "roofline": roofline,
         # the metric's other two parts: MFMA utilisation of the expert GEMMs = roofline.frac; achieved
         # algorithmic HBM rate of the route / dispatch / combine calls (HIP events inside the timed region)
-        "expert_gemm_mfma_util": roofline["frac"],
+        "expert_gemm_mfma_util": roofline["frac_of_mfma_peak"],
         "hbm_calls": hbm,
     }
     if breakdown is not None:
         out["breakdown"] = breakdown
     out["measured_peaks"] = measured_peaks(torch, B)
+    mp = out["measured_peaks"]
+    if w.dtype == I.BF16 and "mfma_bf16_TFLOPs_random_operands" in mp:
+        # context beside the headline fraction (which is against the published peak): what a register-resident
+        # MFMA loop on random operands sustains on this machine, and a plain copy
+        out["roofline"]["frac_of_measured_mfma_random_operands"] = flops / gemm_s / 1e12 / mp["mfma_bf16_TFLOPs_random_operands"]
+        out["roofline"]["frac_of_measured_copy_rate"] = ffn_bytes / gemm_s / 1e12 / mp["copy_TBps"]
     if not args.no_cpu_baseline:
         del x, dy, W1, W2, layer, L
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w, d, forward_only=args.forward_only)
     print(json.dumps(out), flush=True)
+
+
+def gate_skew(w, bias):
+    """How the workload's routing skew was synthesised: the logit bias b = beta * onehot(0) (one hot expert) or
+    b_e = tau * ln q_e with q_e ~ rank^-a (Zipf), recovered from the generator's bias array."""
+    import math
+    if bias is None:
+        return {"kind": "none"}
+    if w.skew == "hot0":
+        return {"kind": "hot0", "target_top1_share": w.skew_param, "beta": float(bias[0])}
+    q0 = 1.0 / sum(r ** -w.skew_param for r in range(1, w.E + 1))
+    return {"kind": "zipf", "exponent": w.skew_param, "tau": float(bias.max()) / math.log(q0)}
 
 
 def measured_peaks(torch, B):

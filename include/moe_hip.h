@@ -34,7 +34,9 @@
  *    are never read by any entry point and are left unwritten.
  *  - Return value: MOE_OK (0) or a negative moe_status.  Argument errors are
  *    detected on the host before anything is enqueued, so outputs are
- *    untouched.  Non-finite logits or keys give undefined routing (no fault).
+ *    untouched.  Non-finite logits or keys give undefined routing values but never an
+ *    out-of-range index: a NaN logit counts as -inf in the top-k, and a slot that NaN
+ *    keys leave unassigned is skipped by moe_dispatch.
  *  - Seeded noise (gate jitter, expert dropout) comes from the counter-based
  *    generator Philox4x32 with 10 rounds (Salmon et al., SC 2011), so a caller or
  *    a checker can reproduce every draw: element i of a tensor uses output word

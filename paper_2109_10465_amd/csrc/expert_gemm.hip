@@ -53,6 +53,17 @@
 #define MOE_GEMM_BK 64
 #endif
 
+// timing probes (never set in the shipped build)
+#ifndef MOE_DBG_STORE
+#define MOE_DBG_STORE 0     // 1: epilogue stores compiled out; 2: every tile's stores land in the expert's first 256 KB
+#endif
+#ifndef MOE_DBG_NOLOAD
+#define MOE_DBG_NOLOAD 0    // 1: no operand loads (the ring is never refilled)
+#endif
+#ifndef MOE_DBG_NOMMA
+#define MOE_DBG_NOMMA 0     // 1: no MFMAs and no fragment reads (loads, waits and barriers only)
+#endif
+
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -84,7 +95,11 @@ template <> struct Mma<bf16_t> {
     static constexpr int KSTEP = 16;  // reduction depth of one MFMA
     typedef bf16x8_t frag;
     __device__ static __forceinline__ f32x16_t mma(frag a, frag b, f32x16_t c) {
+#if MOE_DBG_NOMMA
+        return c;
+#else
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+#endif
     }
 };
 template <> struct Mma<float> {
@@ -113,8 +128,14 @@ __device__ __forceinline__ u32x4_t make_desc(const void* p, uint32_t bytes) {
 // lane l's 16 bytes land at LDS byte address lds_base + 16*l (lds_base is wave
 // uniform and travels in M0).  Written as asm so that the compiler does not
 // serialise every later LDS read behind the load; completion is tracked by
-// hand with vmcnt (see the main loop).
+// hand with vmcnt (see the main loop).  M0 is a reserved register for the
+// compiler: it never keeps a value live in it across other code but writes it
+// immediately before each instruction of its own that reads it, so overwriting
+// it here is safe (naming it as a clobber is rejected as "reserved").
 __device__ __forceinline__ void load_to_lds(u32x4_t desc, uint32_t voff, uint32_t lds_base) {
+#if MOE_DBG_NOLOAD
+    voff = OOB_OFFSET;
+#endif
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
 }
@@ -272,6 +293,20 @@ struct TileOut {
     __amdgpu_buffer_rsrc_t o0, o1, ax;
 };
 
+// epilogue store (the probes either drop it or fold every tile onto the same cache-resident window)
+__device__ __forceinline__ void keep_alive(float4 v) { asm volatile("" :: "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
+__device__ __forceinline__ void keep_alive(uint2 v) { asm volatile("" :: "v"(v.x), "v"(v.y)); }
+template <typename T, typename R>
+__device__ __forceinline__ void tile_store(__amdgpu_buffer_rsrc_t r, uint32_t off, R v) {
+#if MOE_DBG_STORE == 1
+    keep_alive(v);
+#elif MOE_DBG_STORE == 2
+    Vec4buf<T>::store(r, off == BUF_OOB ? off : (off & 0x3ffffu), v);
+#else
+    Vec4buf<T>::store(r, off, v);
+#endif
+}
+
 // One row vector of the output tile: off = byte offset inside the expert's output
 // (BUF_OOB for a column beyond N), o = element index in the whole tensor (for the
 // dropout noise), v = 4 accumulators, aux = the 4 saved derivatives (EPI_MUL only).
@@ -279,7 +314,7 @@ template <typename T, int EPI, int ACT>
 __device__ __forceinline__ void epilogue4(const GemmArgs& p, const TileOut& to, uint32_t off, size_t o,
                                           float (&v)[4], typename Vec4io<T>::raw aux) {
     if constexpr (EPI == EPI_STORE) {
-        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(v));
+        tile_store<T>(to.o0, off, Vec4io<T>::pack(v));
     } else if constexpr (EPI == EPI_H_DACT) {
         float h[4], a[4];
 #pragma unroll
@@ -294,21 +329,21 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& p, const TileOut& to, 
                 a[i] *= sc;     // backward needs no knowledge of it
             }
         }
-        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(a));
-        Vec4buf<T>::store(to.o1, off, Vec4io<T>::pack(h));
+        tile_store<T>(to.o0, off, Vec4io<T>::pack(a));
+        tile_store<T>(to.o1, off, Vec4io<T>::pack(h));
     } else if constexpr (EPI == EPI_H) {
         float h[4], a[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) act_both<sizeof(T) == 2, ACT>(v[i], h[i], a[i]);   // the derivative is dead code here
-        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(h));
+        tile_store<T>(to.o0, off, Vec4io<T>::pack(h));
     } else if constexpr (EPI == EPI_MUL) {
         float a[4];
         Vec4io<T>::unpack(aux, a);
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] *= a[i];
-        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(v));
+        tile_store<T>(to.o0, off, Vec4io<T>::pack(v));
     } else {
-        Vec4buf<float>::store(to.o0, off, make_float4(v[0], v[1], v[2], v[3]));
+        tile_store<float>(to.o0, off, make_float4(v[0], v[1], v[2], v[3]));
     }
 }
 
@@ -513,7 +548,19 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
     // slab 0 of the stream has landed once at most the NS-1 younger slabs are outstanding
     wait_vmcnt<(NS - 1) * SM::LOADS>();
     __syncthreads();
-    typename Mma<T>::frag fa[2][TM], fb[2][TN];
+#ifndef MOE_GEMM_BEARLY
+#define MOE_GEMM_BEARLY 1
+#endif
+    // Two-stage ring with four k-steps per slab (the bf16 tiles): the B half of a stage is released
+    // early.  A wave needs few B fragments (TN per k-step), so it reads those of all four k-steps
+    // during the slab's first step; one barrier later nobody reads the B half again and it is
+    // refilled three k-steps before the A half.  The two halves of a slab are then requested at
+    // different times, there is (almost) always a request in flight, and B has 1.75 slab periods
+    // to arrive instead of one.
+    // (not in the instance whose epilogue keeps saved-derivative rows in registers through the
+    // main loop: the extra fragment registers would spill there)
+    constexpr bool BEARLY = MOE_GEMM_BEARLY && NS == 2 && KS == 4 && EPI != EPI_MUL;
+    typename Mma<T>::frag fa[2][TM], fb[BEARLY ? KS : 2][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i) fa[0][i] = TA::frag(smem_raw, wm * (BM / 2) + i * 32, 0, lane);
 #pragma unroll
@@ -569,6 +616,73 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
             const unsigned char* a_s = smem_raw + stage * SM::STAGE;
             const unsigned char* b_s = a_s + TA::BYTES;
             const int next = stage == NS - 1 ? 0 : stage + 1;
+            if constexpr (BEARLY) {
+                constexpr int NMMA = TM * TN;
+                static_assert(TM + TN <= NMMA && TB::PER_THREAD <= NMMA && TA::PER_THREAD <= NMMA, "one request per MFMA slot");
+                // ---- k-step 0: MFMAs on (fa[0], fb[0]); A fragments of step 1 and B fragments of steps 1..3
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[1][i] = TA::frag(a_s, wm * (BM / 2) + i * 32, 1, lane);
+#pragma unroll
+                for (int ks = 1; ks < KS; ++ks)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) fb[ks][j] = TB::frag(b_s, wn * WCOLS + j * 32, ks, lane);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) acc[i][j] = Mma<T>::mma(fa[0][i], fb[0][j], acc[i][j]);
+#pragma unroll
+                for (int q = 0; q < NMMA; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);   // LDS reads
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // every B fragment of this slab is in registers once this wave's LDS reads have
+                // returned; when all waves are here the B half of the stage is refilled
+                wait_vmcnt_lgkm0<63>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                produce_prepare(stage);
+                // ---- k-step 1: MFMAs on (fa[1], fb[1]); B requests; A fragments of step 2
+#pragma unroll
+                for (int q = 0; q < NMMA; ++q) {
+                    if (q < TB::PER_THREAD) produce_issue(TA::PER_THREAD + q);
+                    if (q < TM) fa[0][q] = TA::frag(a_s, wm * (BM / 2) + q * 32, 2, lane);
+                    acc[q / TN][q % TN] = Mma<T>::mma(fa[1][q / TN], fb[1][q % TN], acc[q / TN][q % TN]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // ---- k-step 2: MFMAs on (fa[0], fb[2]); A fragments of step 3
+#pragma unroll
+                for (int q = 0; q < NMMA; ++q) {
+                    if (q < TM) fa[1][q] = TA::frag(a_s, wm * (BM / 2) + q * 32, 3, lane);
+                    acc[q / TN][q % TN] = Mma<T>::mma(fa[0][q / TN], fb[2][q % TN], acc[q / TN][q % TN]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // ---- k-step 3: the next slab (requested a slab period ago for A, 1.75 for B) has
+                // landed once only the B requests of this slab's step 1 are outstanding (loads complete
+                // in order; anything else that is younger only makes the wait longer); every A
+                // fragment of this slab is in registers, so the A half is refilled; the next
+                // slab's first fragments are fetched under the MFMAs on (fa[1], fb[3])
+                wait_vmcnt_lgkm0<TB::PER_THREAD>();
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                if constexpr (EPI == EPI_MUL) {
+                    if (kt == 0) {
+#pragma unroll
+                        for (int i = 0; i < AUXB; ++i) fetch_aux(i, i);
+                    }
+                }
+                const unsigned char* a_n = smem_raw + next * SM::STAGE;
+#pragma unroll
+                for (int q = 0; q < NMMA; ++q) {
+                    if (q < TA::PER_THREAD) produce_issue(q);
+                    if (q < TM) fa[0][q] = TA::frag(a_n, wm * (BM / 2) + q * 32, 0, lane);
+                    else if (q < TM + TN) fb[0][q - TM] = TB::frag(a_n + TA::BYTES, wn * WCOLS + (q - TM) * 32, 0, lane);
+                    acc[q / TN][q % TN] = Mma<T>::mma(fa[1][q / TN], fb[3][q % TN], acc[q / TN][q % TN]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                stage = next;
+                continue;
+            }
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 const int c = ks & 1, n = c ^ 1;   // KS is even: every slab starts in buffer 0

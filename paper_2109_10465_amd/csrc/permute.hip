@@ -10,7 +10,7 @@
 
 // xd[e,s,:] = x[slot_src[e,s]/k, :]   for s < expert_count[e]
 template <typename T>
-__global__ __launch_bounds__(64 * ROWS_PER_WG) void dispatch_kernel(int d, int k, int C, int n_rows,
+__global__ __launch_bounds__(64 * ROWS_PER_WG) void dispatch_kernel(int d, int k, int C, int n_rows, int n_cand,
                                                        const T* __restrict__ x,
                                                        const int32_t* __restrict__ slot_src,
                                                        const int32_t* __restrict__ expert_count,
@@ -20,7 +20,11 @@ __global__ __launch_bounds__(64 * ROWS_PER_WG) void dispatch_kernel(int d, int k
     if (row >= n_rows) return;
     const int e = row / C, s = row - e * C;
     if (s >= expert_count[e]) return;
-    const int t = slot_src[row] / k;
+    // a slot in use always names a candidate; the check only matters when the routing was
+    // fed non-finite keys (two candidates can then share a rank and leave a slot unwritten)
+    const int cand = slot_src[row];
+    if ((unsigned)cand >= (unsigned)n_cand) return;
+    const int t = cand / k;
     const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)t * d);
     uint4* dst = reinterpret_cast<uint4*>(xd + (size_t)row * d);
     const int nvec = d * (int)sizeof(T) / 16;
@@ -126,10 +130,10 @@ extern "C" int moe_dispatch(const moe_shape* shape, const void* x, const int32_t
     const int grid = ceil_div(n_rows, ROWS_PER_WG);
     hipStream_t st = (hipStream_t)stream;
     if (shape->dtype == MOE_BF16)
-        dispatch_kernel<bf16_t><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows,
+        dispatch_kernel<bf16_t><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows, shape->T * shape->k,
                                                       (const bf16_t*)x, slot_src, expert_count, (bf16_t*)xd);
     else
-        dispatch_kernel<float><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows,
+        dispatch_kernel<float><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows, shape->T * shape->k,
                                                      (const float*)x, slot_src, expert_count, (float*)xd);
     return launch_status();
 }

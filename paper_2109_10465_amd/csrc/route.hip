@@ -118,15 +118,20 @@ __global__ __launch_bounds__(TopkGeom<LPT>::THREADS) void gate_topk_kernel(
             const int t = blockIdx.x * CHUNK + (it0 + u) * G::TPI + slot;
             const bool valid = t < T;   // uniform within a token's lane group
             const float(&l)[4] = lq[u];
-            // the lane's own best two (ascending ids, strict comparisons)
+            // the lane's own best two (ascending ids, strict comparisons).  A NaN logit never
+            // wins a comparison, so for the selection it counts as -inf: among equal values
+            // the smaller id wins, hence every expert id < E beats the sentinel and the
+            // token's k choices are always distinct valid ids, whatever the logits hold
+            // (the probabilities of such a row are NaN; nothing is indexed with them).
             float v0 = -INFINITY, v1 = -INFINITY;
             int i0 = 0x7fffffff, i1 = 0x7fffffff;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int e = e4 + i;
                 if (e < E) {
-                    if (better(l[i], e, v0, i0)) { v1 = v0; i1 = i0; v0 = l[i]; i0 = e; }
-                    else if (better(l[i], e, v1, i1)) { v1 = l[i]; i1 = e; }
+                    const float li = l[i] == l[i] ? l[i] : -INFINITY;
+                    if (better(li, e, v0, i0)) { v1 = v0; i1 = i0; v0 = li; i0 = e; }
+                    else if (better(li, e, v1, i1)) { v1 = li; i1 = e; }
                 }
             }
 #pragma unroll

@@ -298,3 +298,60 @@ def test_step_recorded_as_hip_graph_replays_bit_equal():
             a, b = getattr(Lg, name), getattr(Le, name)
             assert torch.equal(a, b), (seed, name)
         assert adt == Lg.y.dtype and kept.any()
+
+
+@pytest.mark.parametrize("E,k", [(12, 2), (130, 2), (5, 1)])
+def test_non_finite_logits_and_keys_keep_every_index_in_range(E, k):
+    """The ABI promises no fault for non-finite logits or keys (the values are then undefined).
+    A row of NaN logits never wins a comparison; the selection treats NaN as -inf, so the
+    chosen ids stay valid and distinct and everything indexed with them stays in bounds."""
+    T, C, dm = 1000, 150, 64
+    rng = np.random.default_rng(3)
+    lg = (rng.standard_normal((T, E)) * 2).astype(np.float32)
+    keys = rng.random(T, dtype=np.float32)
+    clean = lg.copy()
+    lg[3] = np.nan
+    lg[500] = np.nan
+    lg[10, 1] = np.nan
+    lg[11, :2] = np.inf
+    lg[12] = -np.inf
+    keys[[5, 6, 700]] = np.nan
+    keys[8] = np.inf
+    keys[9] = -np.inf
+    s = B.make_shape(T, dm, dm, E, k, C, I.F32, I.RELU)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    i32, f32 = torch.int32, torch.float32
+    out = dict(probs=torch.empty((T, E), dtype=f32, device="cuda"), expert_idx=torch.full((T, k), -9, dtype=i32, device="cuda"),
+               gate_w=torch.empty((T, k), dtype=f32, device="cuda"), slot=torch.full((T, k), -9, dtype=i32, device="cuda"),
+               expert_count=torch.empty((E,), dtype=i32, device="cuda"), expert_demand=torch.empty((E,), dtype=i32, device="cuda"),
+               slot_src=torch.full((E, C), 0x7ffffff0, dtype=i32, device="cuda"))     # a wild value wherever nothing is written
+    ws = torch.empty(B.moe_workspace_bytes(s), dtype=torch.uint8, device="cuda")
+    print(f"[gpu] non-finite routing inputs: T={T} E={E} k={k} C={C}", flush=True)
+    B.moe_gate_route(s, dev(lg), dev(keys), out["probs"], out["expert_idx"], out["gate_w"], out["slot"],
+                     out["expert_count"], out["expert_demand"], out["slot_src"], ws)
+    torch.cuda.synchronize()
+    e = out["expert_idx"].cpu().numpy()
+    sl = out["slot"].cpu().numpy()
+    src = out["slot_src"].cpu().numpy()
+    assert ((e >= 0) & (e < E)).all()
+    if k == 2:
+        assert (e[:, 0] != e[:, 1]).all()
+    # NaN keys can give two candidates of an expert the same rank: a slot below expert_count may then stay
+    # unwritten (dispatch skips whatever is not a candidate id); everything that IS written is in range
+    assert ((sl >= -1) & (sl < C)).all() and (((src >= -1) & (src < T * k)) | (src == 0x7ffffff0)).all()
+    cnt = out["expert_count"].cpu().numpy()
+    assert ((cnt >= 0) & (cnt <= C)).all() and int(out["expert_demand"].sum()) == T * k
+    # rows without a NaN choose what the definition says (NaN counts as -inf, so row 10 is defined too)
+    ref = O.top_k(np.where(np.isnan(lg), -np.inf, lg)[[0, 1, 2, 10, 999]], k)
+    assert np.array_equal(e[[0, 1, 2, 10, 999]], ref)
+    assert np.array_equal(e[[3, 500]], np.tile(np.arange(k), (2, 1)))       # all-NaN rows: the smallest ids
+    # the consumers of these indices run on them without leaving their buffers
+    x = torch.from_numpy(rng.standard_normal((T, dm)).astype(np.float32)).cuda()
+    xd = torch.zeros((E, C, dm), dtype=f32, device="cuda")
+    y = torch.empty((T, dm), dtype=f32, device="cuda")
+    dl = torch.empty((T, E), dtype=f32, device="cuda")
+    B.moe_dispatch(s, x, out["slot_src"], out["expert_count"], xd)
+    B.moe_combine_fwd(s, xd, out["expert_idx"], out["slot"], out["gate_w"], y)
+    B.moe_gate_bwd(s, out["gate_w"], out["probs"], out["expert_idx"], out["slot"], dl)
+    torch.cuda.synchronize()
+    assert np.isfinite(clean).all()

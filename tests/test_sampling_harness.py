@@ -42,6 +42,40 @@ def test_sampled_checker_accepts_the_oracle_and_rejects_planted_errors(k):
         G.check_sampled(w, d, bad, n_tokens=60, n_cols=8, n_rows=10, fetch_expert=fetch)
 
 
+def test_row_bound_rejects_one_wrong_row_that_the_tensor_norm_lets_through():
+    """bf16 bar (2e-2 over the whole tensor): one entirely wrong row of a few thousand changes the norm by about a
+    per cent and would pass; the per-row bound must reject it, and so must the full comparison of a bf16 layer."""
+    rng = np.random.default_rng(0)
+    want = rng.standard_normal((16384, 64))
+    got = want * (1.0 + 2e-3 * rng.standard_normal(want.shape))          # bf16-like rounding noise
+    G.assert_rows("clean", got, want, 2e-2)
+    bad = got.copy()
+    bad[1234] = rng.standard_normal(64)                                   # a row of something else
+    assert G.rel_l2(bad, want) < 2e-2                                     # the tensor-wide bound does not see it
+    with pytest.raises(AssertionError):
+        G.assert_rows("planted", bad, want, 2e-2)
+    spike = got.copy()
+    spike[7, 3] += 0.5 * np.abs(want).max()                               # one wild element
+    with pytest.raises(AssertionError):
+        G.assert_rows("spike", spike, want, 2e-2)
+    # the same through the comparison the GPU tests use, on a bf16 layer
+    w = I.small("rowbound", 2048, 16, 24, 4, 2, 1100, I.BF16, I.GELU)
+    d = I.make_inputs(w, seed=5)
+    res = full_result(w, d)
+    lg = res["logits"]
+    ref = O.moe_layer(d["x"], d["Wg"], d["bias"], d["W1"], d["W2"], d["rts_keys"], d["dy"], w.k, w.capacity, w.act,
+                      logits=lg)
+    G.compare_full(w, d, res, ref)
+    for name in ["y", "dx"]:
+        bad = dict(res)
+        bad[name] = res[name].copy()
+        t = int(np.nonzero((ref["slot"] >= 0).all(axis=1))[0][3])
+        bad[name][t] = bad[name][t] * 1.5
+        assert G.rel_l2(bad[name], ref[name]) < 2e-2
+        with pytest.raises(AssertionError):
+            G.compare_full(w, d, bad, ref)
+
+
 def test_chained_routing_checker_near_ties_and_planted_errors():
     """The checker of the chained path accepts a run whose logits differ in the
     last bits, accepts either order of a near-tied pair (with the slots that
