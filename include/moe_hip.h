@@ -14,7 +14,9 @@
  * Conventions, valid for every entry point unless stated otherwise
  * ---------------------------------------------------------------
  *  - Every pointer is a DEVICE pointer owned by the caller.  The library
- *    allocates nothing, keeps no state between calls and frees nothing.
+ *    allocates nothing, keeps no state between calls and frees nothing
+ *    (moe_gate_route_static, which brings its own scratch array, is the one
+ *    entry point with memory of its own; see there).
  *    Scratch memory comes from the caller through (ws, ws_bytes); ask
  *    moe_workspace_bytes() for the size.  ws must be 256-byte aligned.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -142,6 +144,26 @@ int moe_gate_route_grouped(const moe_shape* shape, int32_t n_groups, const float
                            float* gate_w, int32_t* slot, int32_t* expert_count,
                            int32_t* expert_demand, int32_t* slot_src, void* ws, size_t ws_bytes,
                            void* stream);
+
+/* moe_gate_route for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * inputs, outputs and results as moe_gate_route (plain routing, one group); the
+ * scratch memory is a device array built into the library instead of a caller
+ * workspace, so the call allocates and frees nothing.  Limits and rules:
+ *  - the shape's routing scratch must fit moe_gate_route_static_max_bytes()
+ *    (4 MiB; enough for T = 65536, k = 2 with any E <= 256), else
+ *    MOE_ERR_WORKSPACE is returned before anything is enqueued;
+ *  - every GPU has one such array and every call on that GPU uses it: calls that
+ *    may overlap on one GPU (two streams, two threads) race and must be ordered
+ *    by the caller; the array keeps the last call's contents and nothing in it
+ *    needs clearing (each call writes all it reads);
+ *  - the array occupies its 4 MiB on every GPU the library runs on until the
+ *    process ends;  MOE_ERR_LAUNCH if the array's address cannot be obtained. */
+size_t moe_gate_route_static_max_bytes(void);
+int moe_gate_route_static(const moe_shape* shape, const float* logits, const float* rts_keys_or_null,
+                          float* probs, int32_t* expert_idx, float* gate_w, int32_t* slot,
+                          int32_t* expert_count, int32_t* expert_demand, int32_t* slot_src,
+                          void* stream);
 
 /* Dispatch (Sec. 3.1: fixed-shape per-expert buffers):
  *   xd[e,s,:] = x[slot_src[e,s] / k, :]  for s < expert_count[e]  (bit copies).

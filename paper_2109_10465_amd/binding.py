@@ -21,6 +21,7 @@ EXPORTS = [
     "moe_utilisation_accumulate", "moe_gate_route_grouped",
     "moe_gate_logits_jitter", "moe_gate_logits_bwd_jitter", "moe_expert_ffn_fwd_dropout",
     "moe_dispatch_gate_logits_bwd", "moe_microbench_mfma_bf16",
+    "moe_gate_route_static", "moe_gate_route_static_max_bytes",
 ]
 
 
@@ -54,7 +55,10 @@ def lib():
         L.moe_capacity.argtypes = [i32, i32, i32, ctypes.c_double]
         L.moe_workspace_bytes.restype = sz
         L.moe_workspace_bytes.argtypes = [shp]
+        L.moe_gate_route_static_max_bytes.restype = sz
+        L.moe_gate_route_static_max_bytes.argtypes = []
         sigs = {
+            "moe_gate_route_static": [shp] + [vp] * 10,
             "moe_gate_logits": [shp] + [vp] * 5,
             "moe_gate_route": [shp] + [vp] * 10 + [sz, vp],
             "moe_dispatch": [shp] + [vp] * 5,
@@ -126,6 +130,17 @@ def moe_gate_route(shape, logits, rts_keys, probs, expert_idx, gate_w, slot, exp
                                 _p(expert_demand), _p(slot_src), _p(ws),
                                 0 if ws is None else ws.numel() * ws.element_size(),
                                 _stream(stream)), "moe_gate_route")
+
+
+def moe_gate_route_static_max_bytes():
+    return lib().moe_gate_route_static_max_bytes()
+
+
+def moe_gate_route_static(shape, logits, rts_keys, probs, expert_idx, gate_w, slot, expert_count,
+                          expert_demand, slot_src, stream=None):
+    _check(lib().moe_gate_route_static(ctypes.byref(shape), _p(logits), _p(rts_keys), _p(probs),
+                                       _p(expert_idx), _p(gate_w), _p(slot), _p(expert_count),
+                                       _p(expert_demand), _p(slot_src), _stream(stream)), "moe_gate_route_static")
 
 
 def moe_gate_route_grouped(shape, n_groups, logits, rts_keys, probs, expert_idx, gate_w, slot, expert_count,

@@ -563,6 +563,51 @@ extern "C" int moe_gate_route(const moe_shape* shape, const float* logits,
                       expert_demand, slot_src, ws, ws_bytes, stream);
 }
 
+// ---------------------------------------------------------------------------
+// moe_gate_route for callers that cannot allocate: the scratch memory (chunk
+// histograms, segment tables, segment-sorted candidate lists) lives in a
+// file-scope device array instead of a caller workspace.  Every GPU holds its
+// own copy of the array at its own address; the address is looked up once per
+// device and that pointer, never the array's name, is what host code passes on.
+// ---------------------------------------------------------------------------
+#define ROUTE_SCRATCH_BYTES (4u << 20)
+static __device__ __align__(256) unsigned char scratch[ROUTE_SCRATCH_BYTES];
+
+#define ROUTE_MAX_DEVICES 64
+static void* scratch_ptr_of_current_device() {
+    static void* ptrs[ROUTE_MAX_DEVICES];      // zero-initialised; written once per device
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= ROUTE_MAX_DEVICES) return nullptr;
+    void* p = __atomic_load_n(&ptrs[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        // a plain address query (no allocation); two threads racing here look up the same address
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        __atomic_store_n(&ptrs[dev], p, __ATOMIC_RELEASE);
+    }
+    return p;
+}
+
+extern "C" size_t moe_gate_route_static_max_bytes(void) { return ROUTE_SCRATCH_BYTES; }
+
+extern "C" int moe_gate_route_static(const moe_shape* shape, const float* logits,
+                                     const float* rts_keys_or_null, float* probs, int32_t* expert_idx,
+                                     float* gate_w, int32_t* slot, int32_t* expert_count,
+                                     int32_t* expert_demand, int32_t* slot_src, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (route_ws_bytes(shape) > ROUTE_SCRATCH_BYTES) return MOE_ERR_WORKSPACE;   // shape beyond the built-in scratch
+    void* ws = scratch_ptr_of_current_device();
+    if (!ws) return MOE_ERR_LAUNCH;
+    // Nothing in the scratch has to start at zero: the histograms, the segment tables and the
+    // candidate lists are all written in full by this call's kernels before they are read, so
+    // what an earlier (possibly larger) call left behind is never seen.
+    return route_impl(shape, 1, logits, rts_keys_or_null, probs, expert_idx, gate_w, slot, expert_count,
+                      expert_demand, slot_src, ws, ROUTE_SCRATCH_BYTES, stream);
+}
+
 extern "C" int moe_gate_route_grouped(const moe_shape* shape, int32_t n_groups, const float* logits,
                                       const float* rts_keys_or_null, float* probs, int32_t* expert_idx,
                                       float* gate_w, int32_t* slot, int32_t* expert_count,
