@@ -58,7 +58,22 @@
 #define MOE_DBG_STORE 0     // 1: epilogue stores compiled out; 2: every tile's stores land in the expert's first 256 KB
 #endif
 #ifndef MOE_DBG_NOLOAD
-#define MOE_DBG_NOLOAD 0    // 1: no operand loads (the ring is never refilled)
+#define MOE_DBG_NOLOAD 0    // 1: operand loads return zeros without memory traffic; 2: only the first tile's first slabs are loaded, the ring then keeps that (real) data
+#endif
+#ifndef MOE_DBG_CLOCK
+#define MOE_DBG_CLOCK 0     // 1: workgroup 0 overwrites the start of its output with per-wave cycle counts
+#endif
+#if MOE_DBG_CLOCK
+#define DBG_CYC() ((long long)__builtin_amdgcn_s_memtime())      // core-clock counter; the result is consumed only after a later full LDS wait
+#define DBG_DT(a, b) ((b) - (a))
+#endif
+#ifndef MOE_DBG_NOBAR
+#define MOE_DBG_NOBAR 0     // 1: no barriers in the bf16 main loop (only meaningful with MOE_DBG_NOLOAD=2: static LDS contents)
+#endif
+#if MOE_DBG_NOBAR
+#define MAIN_BARRIER() ((void)0)
+#else
+#define MAIN_BARRIER() __builtin_amdgcn_s_barrier()
 #endif
 #ifndef MOE_DBG_NOMMA
 #define MOE_DBG_NOMMA 0     // 1: no MFMAs and no fragment reads (loads, waits and barriers only)
@@ -133,7 +148,7 @@ __device__ __forceinline__ u32x4_t make_desc(const void* p, uint32_t bytes) {
 // immediately before each instruction of its own that reads it, so overwriting
 // it here is safe (naming it as a clobber is rejected as "reserved").
 __device__ __forceinline__ void load_to_lds(u32x4_t desc, uint32_t voff, uint32_t lds_base) {
-#if MOE_DBG_NOLOAD
+#if MOE_DBG_NOLOAD == 1
     voff = OOB_OFFSET;
 #endif
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
@@ -457,7 +472,7 @@ struct TileWalk {
 // are already resident when the epilogue of the current one ends, and no
 // workgroup launch or cold first load sits between two tiles.
 template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT, int NWN>
-__global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs p) {
+__global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmArgs p) {   // two waves per SIMD: at most 256 registers
     typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC, NWN> SM;
     typedef typename SM::TA TA;
     typedef typename SM::TB TB;
@@ -490,6 +505,7 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
     pw.start(p, walk_lds);
     bool p_more = pw.next(p);
     int p_kt = 0, p_nk = 0;
+    int dbg_n = 0;   // slabs prepared so far (probe builds only)
     u32x4_t dsA = {0, 0, 0, 0}, dsB = {0, 0, 0, 0};
     typename TA::Plan planA;
     typename TB::Plan planB;
@@ -528,8 +544,12 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
         }
         plds = lds0 + st * SM::STAGE;
         ++p_kt;
+        ++dbg_n;
     };
     auto produce_issue = [&](int i) {   // load i of the prepared slab (i < SM::LOADS; A's loads come first)
+#if MOE_DBG_NOLOAD == 2
+        if (dbg_n > NS) return;
+#endif
         if (i < TA::PER_THREAD) TA::issue_one(planA, pua, p.lda, pk0, pkl, plds, i);
         else TB::issue_one(planB, pub, p.ldb, pk0, pkl, plds + TA::BYTES, i - TA::PER_THREAD);
     };
@@ -567,6 +587,10 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
     for (int j = 0; j < TN; ++j) fb[0][j] = TB::frag(smem_raw + TA::BYTES, wn * WCOLS + j * 32, 0, lane);
     int stage = 0;
 
+#if MOE_DBG_CLOCK
+    long long dbg_tot = 0, dbg_w0 = 0, dbg_w3 = 0, dbg_ep = 0, dbg_n2 = 0, dbg_prev = DBG_CYC(), dbg_a3 = 0, dbg_b3 = 0;
+    const long long dbg_wall0 = wall_clock64();
+#endif
     bool more = true;
     while (more) {
         const int nk = (cw.k_lim + BK - 1) / BK;
@@ -638,22 +662,40 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                 __builtin_amdgcn_sched_barrier(0);
                 // every B fragment of this slab is in registers once this wave's LDS reads have
                 // returned; when all waves are here the B half of the stage is refilled
+#if MOE_DBG_CLOCK
+                const long long dbg_a0 = DBG_CYC();
+#endif
                 wait_vmcnt_lgkm0<63>();
-                __builtin_amdgcn_s_barrier();
+                MAIN_BARRIER();
                 asm volatile("" ::: "memory");
+#if MOE_DBG_CLOCK
+                dbg_w3 += DBG_DT(dbg_a3, dbg_b3);       // the previous event's stamps have arrived by now
+                const long long dbg_b0 = DBG_CYC();
+#endif
                 produce_prepare(stage);
                 // ---- k-step 1: MFMAs on (fa[1], fb[1]); B requests; A fragments of step 2
+                // (a wave issues its instructions strictly one after another, an MFMA holding it for the
+                // MFMA's 32 cycles: only the other wave of the SIMD can fill the matrix pipe meanwhile.  The
+                // requests and fragment reads are therefore dealt evenly over the MFMA slots - a long run of
+                // them in one place leaves the pipe idle whenever both waves are in such a run.)
 #pragma unroll
                 for (int q = 0; q < NMMA; ++q) {
-                    if (q < TB::PER_THREAD) produce_issue(TA::PER_THREAD + q);
-                    if (q < TM) fa[0][q] = TA::frag(a_s, wm * (BM / 2) + q * 32, 2, lane);
+                    constexpr int LSTEP = NMMA / TB::PER_THREAD >= 1 ? NMMA / TB::PER_THREAD : 1;   // a request every LSTEP slots
+                    if (q % LSTEP == 0 && q / LSTEP < TB::PER_THREAD) produce_issue(TA::PER_THREAD + q / LSTEP);
+                    if (NMMA >= 2 * TM ? (q % 2 == 1 && q / 2 < TM) : q < TM) {
+                        const int i = NMMA >= 2 * TM ? q / 2 : q;
+                        fa[0][i] = TA::frag(a_s, wm * (BM / 2) + i * 32, 2, lane);
+                    }
                     acc[q / TN][q % TN] = Mma<T>::mma(fa[1][q / TN], fb[1][q % TN], acc[q / TN][q % TN]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 // ---- k-step 2: MFMAs on (fa[0], fb[2]); A fragments of step 3
 #pragma unroll
                 for (int q = 0; q < NMMA; ++q) {
-                    if (q < TM) fa[1][q] = TA::frag(a_s, wm * (BM / 2) + q * 32, 3, lane);
+                    if (NMMA >= 2 * TM ? (q % 2 == 0 && q / 2 < TM) : q < TM) {
+                        const int i = NMMA >= 2 * TM ? q / 2 : q;
+                        fa[1][i] = TA::frag(a_s, wm * (BM / 2) + i * 32, 3, lane);
+                    }
                     acc[q / TN][q % TN] = Mma<T>::mma(fa[0][q / TN], fb[2][q % TN], acc[q / TN][q % TN]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -662,9 +704,17 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                 // in order; anything else that is younger only makes the wait longer); every A
                 // fragment of this slab is in registers, so the A half is refilled; the next
                 // slab's first fragments are fetched under the MFMAs on (fa[1], fb[3])
+#if MOE_DBG_CLOCK
+                dbg_a3 = DBG_CYC();
+#endif
                 wait_vmcnt_lgkm0<TB::PER_THREAD>();
-                __builtin_amdgcn_s_barrier();
+                MAIN_BARRIER();
                 asm volatile("" ::: "memory");
+#if MOE_DBG_CLOCK
+                dbg_w0 += DBG_DT(dbg_a0, dbg_b0);
+                dbg_tot += DBG_DT(dbg_prev, dbg_a3); dbg_prev = dbg_a3; ++dbg_n2;
+                dbg_b3 = DBG_CYC();
+#endif
                 if constexpr (EPI == EPI_MUL) {
                     if (kt == 0) {
 #pragma unroll
@@ -674,9 +724,19 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                 const unsigned char* a_n = smem_raw + next * SM::STAGE;
 #pragma unroll
                 for (int q = 0; q < NMMA; ++q) {
-                    if (q < TA::PER_THREAD) produce_issue(q);
-                    if (q < TM) fa[0][q] = TA::frag(a_n, wm * (BM / 2) + q * 32, 0, lane);
-                    else if (q < TM + TN) fb[0][q - TM] = TB::frag(a_n + TA::BYTES, wn * WCOLS + (q - TM) * 32, 0, lane);
+                    constexpr int LSTEP = NMMA / TA::PER_THREAD >= 1 ? NMMA / TA::PER_THREAD : 1;
+                    if (q % LSTEP == 0 && q / LSTEP < TA::PER_THREAD) produce_issue(q / LSTEP);
+                    if (NMMA >= 2 * TM) {
+                        // odd slots: one A fragment each; the B fragments (needed first) ride with the first ones
+                        if (q % 2 == 1) {
+                            const int i = q / 2;
+                            if (i < TM) fa[0][i] = TA::frag(a_n, wm * (BM / 2) + i * 32, 0, lane);
+                            if (i < TN) fb[0][i] = TB::frag(a_n + TA::BYTES, wn * WCOLS + i * 32, 0, lane);
+                        }
+                    } else {
+                        if (q < TM) fa[0][q] = TA::frag(a_n, wm * (BM / 2) + q * 32, 0, lane);
+                        else if (q < TM + TN) fb[0][q - TM] = TB::frag(a_n + TA::BYTES, wn * WCOLS + (q - TM) * 32, 0, lane);
+                    }
                     acc[q / TN][q % TN] = Mma<T>::mma(fa[1][q / TN], fb[3][q % TN], acc[q / TN][q % TN]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -744,6 +804,9 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
             stage = next;
         }
 
+#if MOE_DBG_CLOCK
+        const long long dbg_e0 = DBG_CYC();
+#endif
         // ---- epilogue: accumulators -> wave-private LDS strip -> row vectors --------
         // accumulator element v of lane l in a 32x32 tile: column l%32,
         // row 8*(v/4) + 4*(l/32) + v%4; strip s = (i, q) = (s/4, s%4) holds rows i*32 + 8q .. +7.
@@ -802,8 +865,17 @@ __global__ __launch_bounds__(128 * NWN) void grouped_gemm_kernel(const GemmArgs 
                 if (q == 3 && i + AUXB < TM) fetch_aux(i % AUXB, i + AUXB);   // the buffer just used is free again
             }
         }
+#if MOE_DBG_CLOCK
+        { const long long now = DBG_CYC(); dbg_ep += DBG_DT(dbg_e0, now); dbg_tot += DBG_DT(dbg_prev, now); dbg_prev = now; }
+#endif
         more = cw.next(p);
     }
+#if MOE_DBG_CLOCK
+    if (blockIdx.x == 0 && lane == 0) {
+        long long* o = (long long*)p.out0 + wave * 8;
+        o[0] = dbg_tot; o[1] = wall_clock64() - dbg_wall0; o[2] = dbg_w0; o[3] = dbg_w3; o[4] = dbg_ep; o[5] = dbg_n2;
+    }
+#endif
     // the zero-fill loads requested past the end of the stream target this
     // workgroup's LDS: wait for them before the workgroup retires
     wait_vmcnt<0>();
@@ -837,7 +909,10 @@ static void launch_gemm(GemmArgs p, int E, hipStream_t st) {
     // in groups of 8 so that every XCD gets the same number; never more than
     // there could be tiles
     const long long most = ((long long)E * p.tiles_m * p.tiles_n + 7) / 8;
-    int per_xcd = num_cus() / 8;
+#ifndef MOE_GEMM_WGPC
+#define MOE_GEMM_WGPC 1
+#endif
+    int per_xcd = num_cus() / 8 * MOE_GEMM_WGPC;   // workgroups per CU that fit its LDS
     if (per_xcd < 1) per_xcd = 1;
     if (per_xcd > most) per_xcd = (int)most;
     const size_t smem = SM::BYTES + WALK_BYTES;
