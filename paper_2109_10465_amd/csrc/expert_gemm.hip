@@ -53,32 +53,6 @@
 #define MOE_GEMM_BK 64
 #endif
 
-// timing probes (never set in the shipped build)
-#ifndef MOE_DBG_STORE
-#define MOE_DBG_STORE 0     // 1: epilogue stores compiled out; 2: every tile's stores land in the expert's first 256 KB
-#endif
-#ifndef MOE_DBG_NOLOAD
-#define MOE_DBG_NOLOAD 0    // 1: operand loads return zeros without memory traffic; 2: only the first tile's first slabs are loaded, the ring then keeps that (real) data
-#endif
-#ifndef MOE_DBG_CLOCK
-#define MOE_DBG_CLOCK 0     // 1: workgroup 0 overwrites the start of its output with per-wave cycle counts
-#endif
-#if MOE_DBG_CLOCK
-#define DBG_CYC() ((long long)__builtin_amdgcn_s_memtime())      // core-clock counter; the result is consumed only after a later full LDS wait
-#define DBG_DT(a, b) ((b) - (a))
-#endif
-#ifndef MOE_DBG_NOBAR
-#define MOE_DBG_NOBAR 0     // 1: no barriers in the bf16 main loop (only meaningful with MOE_DBG_NOLOAD=2: static LDS contents)
-#endif
-#if MOE_DBG_NOBAR
-#define MAIN_BARRIER() ((void)0)
-#else
-#define MAIN_BARRIER() __builtin_amdgcn_s_barrier()
-#endif
-#ifndef MOE_DBG_NOMMA
-#define MOE_DBG_NOMMA 0     // 1: no MFMAs and no fragment reads (loads, waits and barriers only)
-#endif
-
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
@@ -110,11 +84,7 @@ template <> struct Mma<bf16_t> {
     static constexpr int KSTEP = 16;  // reduction depth of one MFMA
     typedef bf16x8_t frag;
     __device__ static __forceinline__ f32x16_t mma(frag a, frag b, f32x16_t c) {
-#if MOE_DBG_NOMMA
-        return c;
-#else
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-#endif
     }
 };
 template <> struct Mma<float> {
@@ -148,9 +118,6 @@ __device__ __forceinline__ u32x4_t make_desc(const void* p, uint32_t bytes) {
 // immediately before each instruction of its own that reads it, so overwriting
 // it here is safe (naming it as a clobber is rejected as "reserved").
 __device__ __forceinline__ void load_to_lds(u32x4_t desc, uint32_t voff, uint32_t lds_base) {
-#if MOE_DBG_NOLOAD == 1
-    voff = OOB_OFFSET;
-#endif
     asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                  :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
 }
@@ -308,20 +275,6 @@ struct TileOut {
     __amdgpu_buffer_rsrc_t o0, o1, ax;
 };
 
-// epilogue store (the probes either drop it or fold every tile onto the same cache-resident window)
-__device__ __forceinline__ void keep_alive(float4 v) { asm volatile("" :: "v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w)); }
-__device__ __forceinline__ void keep_alive(uint2 v) { asm volatile("" :: "v"(v.x), "v"(v.y)); }
-template <typename T, typename R>
-__device__ __forceinline__ void tile_store(__amdgpu_buffer_rsrc_t r, uint32_t off, R v) {
-#if MOE_DBG_STORE == 1
-    keep_alive(v);
-#elif MOE_DBG_STORE == 2
-    Vec4buf<T>::store(r, off == BUF_OOB ? off : (off & 0x3ffffu), v);
-#else
-    Vec4buf<T>::store(r, off, v);
-#endif
-}
-
 // One row vector of the output tile: off = byte offset inside the expert's output
 // (BUF_OOB for a column beyond N), o = element index in the whole tensor (for the
 // dropout noise), v = 4 accumulators, aux = the 4 saved derivatives (EPI_MUL only).
@@ -329,7 +282,7 @@ template <typename T, int EPI, int ACT>
 __device__ __forceinline__ void epilogue4(const GemmArgs& p, const TileOut& to, uint32_t off, size_t o,
                                           float (&v)[4], typename Vec4io<T>::raw aux) {
     if constexpr (EPI == EPI_STORE) {
-        tile_store<T>(to.o0, off, Vec4io<T>::pack(v));
+        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(v));
     } else if constexpr (EPI == EPI_H_DACT) {
         float h[4], a[4];
 #pragma unroll
@@ -344,21 +297,21 @@ __device__ __forceinline__ void epilogue4(const GemmArgs& p, const TileOut& to, 
                 a[i] *= sc;     // backward needs no knowledge of it
             }
         }
-        tile_store<T>(to.o0, off, Vec4io<T>::pack(a));
-        tile_store<T>(to.o1, off, Vec4io<T>::pack(h));
+        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(a));
+        Vec4buf<T>::store(to.o1, off, Vec4io<T>::pack(h));
     } else if constexpr (EPI == EPI_H) {
         float h[4], a[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) act_both<sizeof(T) == 2, ACT>(v[i], h[i], a[i]);   // the derivative is dead code here
-        tile_store<T>(to.o0, off, Vec4io<T>::pack(h));
+        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(h));
     } else if constexpr (EPI == EPI_MUL) {
         float a[4];
         Vec4io<T>::unpack(aux, a);
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] *= a[i];
-        tile_store<T>(to.o0, off, Vec4io<T>::pack(v));
+        Vec4buf<T>::store(to.o0, off, Vec4io<T>::pack(v));
     } else {
-        tile_store<float>(to.o0, off, make_float4(v[0], v[1], v[2], v[3]));
+        Vec4buf<float>::store(to.o0, off, make_float4(v[0], v[1], v[2], v[3]));
     }
 }
 
@@ -505,7 +458,6 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
     pw.start(p, walk_lds);
     bool p_more = pw.next(p);
     int p_kt = 0, p_nk = 0;
-    int dbg_n = 0;   // slabs prepared so far (probe builds only)
     u32x4_t dsA = {0, 0, 0, 0}, dsB = {0, 0, 0, 0};
     typename TA::Plan planA;
     typename TB::Plan planB;
@@ -544,12 +496,8 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
         }
         plds = lds0 + st * SM::STAGE;
         ++p_kt;
-        ++dbg_n;
     };
     auto produce_issue = [&](int i) {   // load i of the prepared slab (i < SM::LOADS; A's loads come first)
-#if MOE_DBG_NOLOAD == 2
-        if (dbg_n > NS) return;
-#endif
         if (i < TA::PER_THREAD) TA::issue_one(planA, pua, p.lda, pk0, pkl, plds, i);
         else TB::issue_one(planB, pub, p.ldb, pk0, pkl, plds + TA::BYTES, i - TA::PER_THREAD);
     };
@@ -587,10 +535,6 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
     for (int j = 0; j < TN; ++j) fb[0][j] = TB::frag(smem_raw + TA::BYTES, wn * WCOLS + j * 32, 0, lane);
     int stage = 0;
 
-#if MOE_DBG_CLOCK
-    long long dbg_tot = 0, dbg_w0 = 0, dbg_w3 = 0, dbg_ep = 0, dbg_n2 = 0, dbg_prev = DBG_CYC(), dbg_a3 = 0, dbg_b3 = 0;
-    const long long dbg_wall0 = wall_clock64();
-#endif
     bool more = true;
     while (more) {
         const int nk = (cw.k_lim + BK - 1) / BK;
@@ -662,16 +606,9 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
                 __builtin_amdgcn_sched_barrier(0);
                 // every B fragment of this slab is in registers once this wave's LDS reads have
                 // returned; when all waves are here the B half of the stage is refilled
-#if MOE_DBG_CLOCK
-                const long long dbg_a0 = DBG_CYC();
-#endif
                 wait_vmcnt_lgkm0<63>();
-                MAIN_BARRIER();
+                __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-#if MOE_DBG_CLOCK
-                dbg_w3 += DBG_DT(dbg_a3, dbg_b3);       // the previous event's stamps have arrived by now
-                const long long dbg_b0 = DBG_CYC();
-#endif
                 produce_prepare(stage);
                 // ---- k-step 1: MFMAs on (fa[1], fb[1]); B requests; A fragments of step 2
                 // (a wave issues its instructions strictly one after another, an MFMA holding it for the
@@ -704,17 +641,9 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
                 // in order; anything else that is younger only makes the wait longer); every A
                 // fragment of this slab is in registers, so the A half is refilled; the next
                 // slab's first fragments are fetched under the MFMAs on (fa[1], fb[3])
-#if MOE_DBG_CLOCK
-                dbg_a3 = DBG_CYC();
-#endif
                 wait_vmcnt_lgkm0<TB::PER_THREAD>();
-                MAIN_BARRIER();
+                __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
-#if MOE_DBG_CLOCK
-                dbg_w0 += DBG_DT(dbg_a0, dbg_b0);
-                dbg_tot += DBG_DT(dbg_prev, dbg_a3); dbg_prev = dbg_a3; ++dbg_n2;
-                dbg_b3 = DBG_CYC();
-#endif
                 if constexpr (EPI == EPI_MUL) {
                     if (kt == 0) {
 #pragma unroll
@@ -804,9 +733,6 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
             stage = next;
         }
 
-#if MOE_DBG_CLOCK
-        const long long dbg_e0 = DBG_CYC();
-#endif
         // ---- epilogue: accumulators -> wave-private LDS strip -> row vectors --------
         // accumulator element v of lane l in a 32x32 tile: column l%32,
         // row 8*(v/4) + 4*(l/32) + v%4; strip s = (i, q) = (s/4, s%4) holds rows i*32 + 8q .. +7.
@@ -865,17 +791,8 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
                 if (q == 3 && i + AUXB < TM) fetch_aux(i % AUXB, i + AUXB);   // the buffer just used is free again
             }
         }
-#if MOE_DBG_CLOCK
-        { const long long now = DBG_CYC(); dbg_ep += DBG_DT(dbg_e0, now); dbg_tot += DBG_DT(dbg_prev, now); dbg_prev = now; }
-#endif
         more = cw.next(p);
     }
-#if MOE_DBG_CLOCK
-    if (blockIdx.x == 0 && lane == 0) {
-        long long* o = (long long*)p.out0 + wave * 8;
-        o[0] = dbg_tot; o[1] = wall_clock64() - dbg_wall0; o[2] = dbg_w0; o[3] = dbg_w3; o[4] = dbg_ep; o[5] = dbg_n2;
-    }
-#endif
     // the zero-fill loads requested past the end of the stream target this
     // workgroup's LDS: wait for them before the workgroup retires
     wait_vmcnt<0>();
