@@ -425,7 +425,7 @@ struct TileWalk {
 // are already resident when the epilogue of the current one ends, and no
 // workgroup launch or cold first load sits between two tiles.
 template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT, int NWN>
-__global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmArgs p) {   // two waves per SIMD: at most 256 registers
+__device__ __forceinline__ void gemm_body(const GemmArgs& p) {
     typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC, NWN> SM;
     typedef typename SM::TA TA;
     typedef typename SM::TB TB;
@@ -527,7 +527,10 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
     // to arrive instead of one.
     // (not in the instance whose epilogue keeps saved-derivative rows in registers through the
     // main loop: the extra fragment registers would spill there)
-    constexpr bool BEARLY = MOE_GEMM_BEARLY && NS == 2 && KS == 4 && EPI != EPI_MUL;
+#ifndef MOE_GEMM_DZ_BEARLY
+#define MOE_GEMM_DZ_BEARLY 0
+#endif
+    constexpr bool BEARLY = MOE_GEMM_BEARLY && NS == 2 && KS == 4 && (EPI != EPI_MUL || MOE_GEMM_DZ_BEARLY);
     typename Mma<T>::frag fa[2][TM], fb[BEARLY ? KS : 2][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i) fa[0][i] = TA::frag(smem_raw, wm * (BM / 2) + i * 32, 0, lane);
@@ -546,7 +549,10 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
         // EPI_MUL: the saved derivative does not depend on the product.  The rows of
         // the first two 32-row blocks are requested now and ride in registers through
         // the main loop; the later blocks are requested while earlier ones are written.
-        constexpr int AUXB = EPI == EPI_MUL ? (TM < 2 ? TM : 2) : 1;
+#ifndef MOE_GEMM_AUXB
+#define MOE_GEMM_AUXB 2
+#endif
+        constexpr int AUXB = EPI == EPI_MUL ? (TM < MOE_GEMM_AUXB ? TM : MOE_GEMM_AUXB) : 1;
         raw aux[AUXB][EPI == EPI_MUL ? 4 : 1][EPI == EPI_MUL ? NIT : 1];
         constexpr uint32_t OSZ = EPI == EPI_F32 ? 4u : (uint32_t)sizeof(T);   // bytes per output element
         const size_t obytes = (size_t)m_lim * p.ldo * OSZ;                    // the expert's rows in use
@@ -798,49 +804,95 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
     wait_vmcnt<0>();
 }
 
-// Number of compute units (cached; the library keeps no other state).
+template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT, int NWN>
+__global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmArgs p) {   // two waves per SIMD: at most 256 registers
+    gemm_body<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN>(p);
+}
+
+// Two independent grouped GEMMs in one launch: every workgroup walks its tiles of the
+// first, then its tiles of the second.  Nothing is synchronised between workgroups (the
+// two products must not depend on each other), so a workgroup that is done with the first
+// starts the second at once: one launch, one ramp-up and one tail instead of two, and the
+// workgroups drift apart, which spreads the store bursts of their epilogues.
+template <typename T, int BM, int BN, int BK, bool A1, bool B1, int EPI1, bool A2, bool B2, int EPI2, int NWN>
+__global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_pair_kernel(const GemmArgs p1, const GemmArgs p2) {
+    gemm_body<T, BM, BN, BK, A1, B1, EPI1, 0, NWN>(p1);
+    __syncthreads();      // every wave is done with the ring and the tile table of the first product
+    gemm_body<T, BM, BN, BK, A2, B2, EPI2, 0, NWN>(p2);
+}
+
+// Number of compute units of the current device (looked up once per device).
 static int num_cus() {
-    static int n = 0;
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = __atomic_load_n(&cached[dev], __ATOMIC_RELAXED);
     if (n == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            n = v;
-        else
-            n = 256;
+        int v = 0;
+        n = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+        __atomic_store_n(&cached[dev], n, __ATOMIC_RELAXED);
     }
     return n;
+}
+
+// A kernel that uses more than 64 KB of the CU's 160 KB LDS has to opt in, once per kernel
+// instance and device (`done` is that instance's bit mask over device ids).
+static bool lds_opt_in(const void* kern, size_t smem, unsigned long long* done) {
+    if (smem <= 64 * 1024) return true;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    if (__atomic_load_n(done, __ATOMIC_ACQUIRE) >> dev & 1ull) return true;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    __atomic_fetch_or(done, 1ull << dev, __ATOMIC_RELEASE);
+    return true;
 }
 
 #ifndef MOE_GEMM_NWN
 #define MOE_GEMM_NWN 4
 #endif
+// one persistent workgroup per CU (its LDS footprint allows no second one), in groups of 8 so
+// that every XCD gets the same number; never more than there could be tiles
+static int gemm_grid(long long tiles) {
+    const long long most = (tiles + 7) / 8;
+    int per_xcd = num_cus() / 8;
+    if (per_xcd < 1) per_xcd = 1;
+    if (per_xcd > most) per_xcd = (int)most;
+    return per_xcd * 8;
+}
+
 template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT = 0>
-static void launch_gemm(GemmArgs p, int E, hipStream_t st) {
+static bool launch_gemm(GemmArgs p, int E, hipStream_t st) {
     constexpr int NWN = sizeof(T) == 2 ? MOE_GEMM_NWN : 2;
     typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC, NWN> SM;
     p.tiles_m = ceil_div(p.M, BM);
     p.tiles_n = ceil_div(p.N, BN);
     p.E = E;
-    // one persistent workgroup per CU (its LDS footprint allows no second one),
-    // in groups of 8 so that every XCD gets the same number; never more than
-    // there could be tiles
-    const long long most = ((long long)E * p.tiles_m * p.tiles_n + 7) / 8;
-#ifndef MOE_GEMM_WGPC
-#define MOE_GEMM_WGPC 1
-#endif
-    int per_xcd = num_cus() / 8 * MOE_GEMM_WGPC;   // workgroups per CU that fit its LDS
-    if (per_xcd < 1) per_xcd = 1;
-    if (per_xcd > most) per_xcd = (int)most;
     const size_t smem = SM::BYTES + WALK_BYTES;
     auto kern = grouped_gemm_kernel<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN>;
-    if (smem > 64 * 1024) {
-        // opt in (once per kernel instance) to more than 64 KB of the CU's 160 KB LDS
-        static const hipError_t attr = hipFuncSetAttribute(
-            (const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        (void)attr;
-    }
-    kern<<<per_xcd * 8, SM::NT, smem, st>>>(p);
+    static unsigned long long opted = 0;
+    if (!lds_opt_in((const void*)kern, smem, &opted)) return false;
+    kern<<<gemm_grid((long long)E * p.tiles_m * p.tiles_n), SM::NT, smem, st>>>(p);
+    return true;
+}
+
+template <typename T, int BM, int BN, int BK, bool A1, bool B1, int EPI1, bool A2, bool B2, int EPI2>
+static bool launch_gemm_pair(GemmArgs p1, GemmArgs p2, int E, hipStream_t st) {
+    constexpr int NWN = sizeof(T) == 2 ? MOE_GEMM_NWN : 2;
+    typedef GemmSmem<T, BM, BN, BK, A1, B1, NWN> SM1;
+    typedef GemmSmem<T, BM, BN, BK, A2, B2, NWN> SM2;
+    static_assert(SM1::NT == SM2::NT, "one workgroup shape");
+    p1.tiles_m = ceil_div(p1.M, BM); p1.tiles_n = ceil_div(p1.N, BN); p1.E = E;
+    p2.tiles_m = ceil_div(p2.M, BM); p2.tiles_n = ceil_div(p2.N, BN); p2.E = E;
+    const size_t smem = (SM1::BYTES > SM2::BYTES ? SM1::BYTES : SM2::BYTES) + WALK_BYTES;
+    auto kern = grouped_gemm_pair_kernel<T, BM, BN, BK, A1, B1, EPI1, A2, B2, EPI2, NWN>;
+    static unsigned long long opted = 0;
+    if (!lds_opt_in((const void*)kern, smem, &opted)) return false;
+    const long long t1 = (long long)E * p1.tiles_m * p1.tiles_n, t2 = (long long)E * p2.tiles_m * p2.tiles_n;
+    kern<<<gemm_grid(t1 > t2 ? t1 : t2), SM1::NT, smem, st>>>(p1, p2);
+    return true;
 }
 
 size_t ffn_bwd_ws_bytes(const moe_shape* s) {
@@ -856,7 +908,7 @@ static int check_slice_limits(const moe_shape* s) {
 }
 
 template <typename T, int BM, int BN, int BK>
-static void ffn_fwd(const moe_shape* s, const void* xd, const int32_t* cnt, const void* W1,
+static bool ffn_fwd(const moe_shape* s, const void* xd, const int32_t* cnt, const void* W1,
                     const void* W2, void* h, void* a, void* yd, float drop_p, uint64_t seed, hipStream_t st) {
     const int E = s->E, C = s->capacity, d = s->d_model, f = s->d_ff;
     GemmArgs p = {};
@@ -871,54 +923,56 @@ static void ffn_fwd(const moe_shape* s, const void* xd, const int32_t* cnt, cons
     p.B = W1; p.ldb = f; p.strideB = (long long)d * f;
     p.out0 = a; p.out1 = h; p.ldo = f; p.strideO = (long long)C * f;
     p.M = C; p.N = f; p.K = d;
+    bool ok;
     if (!a) {   // forward-only: the derivative is neither computed nor stored
         p.out0 = h; p.out1 = nullptr;
-        if (s->act == MOE_RELU) launch_gemm<T, BM, BN, BK, true, false, EPI_H, MOE_RELU>(p, E, st);
-        else launch_gemm<T, BM, BN, BK, true, false, EPI_H, MOE_GELU>(p, E, st);
-    } else if (s->act == MOE_RELU) launch_gemm<T, BM, BN, BK, true, false, EPI_H_DACT, MOE_RELU>(p, E, st);
-    else launch_gemm<T, BM, BN, BK, true, false, EPI_H_DACT, MOE_GELU>(p, E, st);
+        if (s->act == MOE_RELU) ok = launch_gemm<T, BM, BN, BK, true, false, EPI_H, MOE_RELU>(p, E, st);
+        else ok = launch_gemm<T, BM, BN, BK, true, false, EPI_H, MOE_GELU>(p, E, st);
+    } else if (s->act == MOE_RELU) ok = launch_gemm<T, BM, BN, BK, true, false, EPI_H_DACT, MOE_RELU>(p, E, st);
+    else ok = launch_gemm<T, BM, BN, BK, true, false, EPI_H_DACT, MOE_GELU>(p, E, st);
+    if (!ok) return false;
     // yd = h W2
     p.A = h; p.lda = f; p.strideA = (long long)C * f;
     p.B = W2; p.ldb = d; p.strideB = (long long)f * d;
     p.out0 = yd; p.out1 = nullptr; p.ldo = d; p.strideO = (long long)C * d;
     p.M = C; p.N = d; p.K = f;
     p.drop_thr = 0;
-    launch_gemm<T, BM, BN, BK, true, false, EPI_STORE>(p, E, st);
+    return launch_gemm<T, BM, BN, BK, true, false, EPI_STORE>(p, E, st);
 }
 
 template <typename T, int BM, int BN, int BK>
-static void ffn_bwd(const moe_shape* s, const void* dyd, const void* xd, const void* h,
+static bool ffn_bwd(const moe_shape* s, const void* dyd, const void* xd, const void* h,
                     const void* a, const int32_t* cnt, const void* W1, const void* W2, void* dxd,
                     float* dW1, float* dW2, void* dz, hipStream_t st) {
     const int E = s->E, C = s->capacity, d = s->d_model, f = s->d_ff;
-    GemmArgs p = {};
-    p.expert_count = cnt;
+    // Four products in two launches.  dW2 needs only h and dyd, so it shares a launch with dz;
+    // dxd and dW1 both need dz and share the second one.
+    GemmArgs p = {}, q = {};
+    p.expert_count = q.expert_count = cnt;
     // dz = (dyd W2^T) .* a:  B(r = n in f, k in d) = W2[n*d + k]
     p.var_k = 0;
     p.A = dyd; p.lda = d; p.strideA = (long long)C * d;
     p.B = W2; p.ldb = d; p.strideB = (long long)f * d;
     p.out0 = dz; p.aux = a; p.ldo = f; p.strideO = (long long)C * f;
     p.M = C; p.N = f; p.K = d;
-    launch_gemm<T, BM, BN, BK, true, true, EPI_MUL>(p, E, st);
+    // dW2[f,d] = h^T dyd:  A(r = m in f, k = row) = h[k*f + m], B(r = n in d, k) = dyd[k*d + n]
+    q.var_k = 1;
+    q.A = h; q.lda = f; q.strideA = (long long)C * f;
+    q.B = dyd; q.ldb = d; q.strideB = (long long)C * d;
+    q.out0 = dW2; q.ldo = d; q.strideO = (long long)f * d;
+    q.M = f; q.N = d; q.K = C;
+    if (!launch_gemm_pair<T, BM, BN, BK, true, true, EPI_MUL, false, false, EPI_F32>(p, q, E, st)) return false;
     // dxd = dz W1^T:  B(r = n in d, k in f) = W1[n*f + k]
     p.A = dz; p.lda = f; p.strideA = (long long)C * f;
     p.B = W1; p.ldb = f; p.strideB = (long long)d * f;
     p.out0 = dxd; p.aux = nullptr; p.ldo = d; p.strideO = (long long)C * d;
     p.M = C; p.N = d; p.K = f;
-    launch_gemm<T, BM, BN, BK, true, true, EPI_STORE>(p, E, st);
-    // dW2[f,d] = h^T dyd:  A(r = m in f, k = row) = h[k*f + m], B(r = n in d, k) = dyd[k*d + n]
-    p.var_k = 1;
-    p.A = h; p.lda = f; p.strideA = (long long)C * f;
-    p.B = dyd; p.ldb = d; p.strideB = (long long)C * d;
-    p.out0 = dW2; p.ldo = d; p.strideO = (long long)f * d;
-    p.M = f; p.N = d; p.K = C;
-    launch_gemm<T, BM, BN, BK, false, false, EPI_F32>(p, E, st);
     // dW1[d,f] = xd^T dz
-    p.A = xd; p.lda = d; p.strideA = (long long)C * d;
-    p.B = dz; p.ldb = f; p.strideB = (long long)C * f;
-    p.out0 = dW1; p.ldo = f; p.strideO = (long long)d * f;
-    p.M = d; p.N = f; p.K = C;
-    launch_gemm<T, BM, BN, BK, false, false, EPI_F32>(p, E, st);
+    q.A = xd; q.lda = d; q.strideA = (long long)C * d;
+    q.B = dz; q.ldb = f; q.strideB = (long long)C * f;
+    q.out0 = dW1; q.ldo = f; q.strideO = (long long)d * f;
+    q.M = d; q.N = f; q.K = C;
+    return launch_gemm_pair<T, BM, BN, BK, true, true, EPI_STORE, false, false, EPI_F32>(p, q, E, st);
 }
 
 static int ffn_fwd_impl(const moe_shape* shape, const void* xd, const int32_t* expert_count,
@@ -932,11 +986,10 @@ static int ffn_fwd_impl(const moe_shape* shape, const void* xd, const int32_t* e
     if (drop_p > 0.0f && !dact_saved) return MOE_ERR_NULL;      // dropout is a training feature
     if (drop_p > 0.0f && floor((double)drop_p * 4294967296.0) < 1.0) drop_p = 0.0f;   // below one part in 2^32
     hipStream_t st = (hipStream_t)stream;
-    if (shape->dtype == MOE_BF16)
-        ffn_fwd<bf16_t, MOE_GEMM_BM, MOE_GEMM_BN, MOE_GEMM_BK>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, drop_p, seed, st);
-    else
-        ffn_fwd<float, 128, 128, 16>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, drop_p, seed, st);
-    return launch_status();
+    const bool ok = shape->dtype == MOE_BF16
+        ? ffn_fwd<bf16_t, MOE_GEMM_BM, MOE_GEMM_BN, MOE_GEMM_BK>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, drop_p, seed, st)
+        : ffn_fwd<float, 128, 128, 16>(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, drop_p, seed, st);
+    return ok ? launch_status() : MOE_ERR_LAUNCH;
 }
 
 extern "C" int moe_expert_ffn_fwd(const moe_shape* shape, const void* xd,
@@ -964,9 +1017,8 @@ extern "C" int moe_expert_ffn_bwd(const moe_shape* shape, const void* dyd, const
         return MOE_ERR_NULL;
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < ffn_bwd_ws_bytes(shape)) return MOE_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    if (shape->dtype == MOE_BF16)
-        ffn_bwd<bf16_t, MOE_GEMM_BM, MOE_GEMM_BN, MOE_GEMM_BK>(shape, dyd, xd, h_saved, dact_saved, expert_count, W1, W2, dxd, dW1, dW2, ws, st);
-    else
-        ffn_bwd<float, 128, 128, 16>(shape, dyd, xd, h_saved, dact_saved, expert_count, W1, W2, dxd, dW1, dW2, ws, st);
-    return launch_status();
+    const bool ok = shape->dtype == MOE_BF16
+        ? ffn_bwd<bf16_t, MOE_GEMM_BM, MOE_GEMM_BN, MOE_GEMM_BK>(shape, dyd, xd, h_saved, dact_saved, expert_count, W1, W2, dxd, dW1, dW2, ws, st)
+        : ffn_bwd<float, 128, 128, 16>(shape, dyd, xd, h_saved, dact_saved, expert_count, W1, W2, dxd, dW1, dW2, ws, st);
+    return ok ? launch_status() : MOE_ERR_LAUNCH;
 }

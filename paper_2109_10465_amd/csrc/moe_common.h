@@ -249,6 +249,9 @@ static inline size_t elem_bytes(int dtype) { return dtype == MOE_BF16 ? 2 : 4; }
 
 // Validates the shape limits documented in moe_hip.h.
 static inline int check_shape(const moe_shape* s) {
+    // every entry point starts here: an error that an earlier, unrelated HIP call left behind is
+    // dropped now, so that launch_status() at the end reports this call's launches only
+    (void)hipGetLastError();
     if (!s) return MOE_ERR_NULL;
     if (s->dtype != MOE_F32 && s->dtype != MOE_BF16) return MOE_ERR_DTYPE;
     if (s->act != MOE_RELU && s->act != MOE_GELU) return MOE_ERR_DTYPE;
