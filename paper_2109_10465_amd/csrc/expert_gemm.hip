@@ -177,25 +177,30 @@ template <typename T, int BR, int BK, bool KC, int NT> struct Tile {
     __device__ static __forceinline__ u32x4_t desc(const T* g, int ld, int r_lim, int k_lim) {
         return make_desc(g, (uint32_t)(KC ? r_lim : k_lim) * (uint32_t)ld * (uint32_t)sizeof(T));
     }
-    // Issue this thread's loads of the slab at reduction offset k0 into the stage at lds_base.
-    __device__ static __forceinline__ void issue(const Plan& pl, u32x4_t ds, int ld, int k0, int k_lim,
-                                                 uint32_t lds_base) {
-        const uint32_t kstep = (uint32_t)(KC ? k0 : k0 * ld) * (uint32_t)sizeof(T);
-        const uint32_t wave_base = lds_base + (threadIdx.x >> 6) * 1024;
-#pragma unroll
-        for (int i = 0; i < PER_THREAD; ++i) {
-            uint32_t off = pl.voff[i] + kstep;
-            if (KC) off = pl.kcol[i] + k0 < k_lim ? off : OOB_OFFSET;
-            load_to_lds(ds, off, __builtin_amdgcn_readfirstlane(wave_base + i * NT * 16));
-        }
+    // Byte shift of the slab at reduction offset k0 inside the operand; it is applied to the
+    // descriptor (scalar work, once per slab), not to every lane's offset.
+    __device__ static __forceinline__ uint32_t slab_shift(int ld, int k0) {
+        return (uint32_t)(KC ? k0 : k0 * ld) * (uint32_t)sizeof(T);
     }
-    // The i-th of this thread's loads alone (to spread a slab's requests between MFMAs).
-    __device__ static __forceinline__ void issue_one(const Plan& pl, u32x4_t ds, int ld, int k0, int k_lim,
-                                                     uint32_t lds_base, int i) {
-        const uint32_t kstep = (uint32_t)(KC ? k0 : k0 * ld) * (uint32_t)sizeof(T);
+    // The descriptor of one slab: base moved to the slab's first reduction entry.  For an
+    // r-contiguous operand the range shrinks by the same amount, so that "reduction row < k_lim"
+    // stays the descriptor's range check; for a k-contiguous operand the range (rows < r_lim)
+    // is kept - every in-range row stays inside the tensor as long as the slab does.
+    __device__ static __forceinline__ u32x4_t slab_desc(u32x4_t d, uint32_t shift) {
+        const uint64_t base = ((uint64_t)(d[1] & 0xffffu) << 32 | d[0]) + shift;
+        d[0] = (uint32_t)base;
+        d[1] = (d[1] & 0xffff0000u) | (uint32_t)(base >> 32);
+        if (!KC) d[2] = d[2] > shift ? d[2] - shift : 0u;
+        return d;
+    }
+    // The i-th of this thread's loads of the slab whose descriptor is ds, into the stage at lds_base.
+    // KG: the reduction length is not a multiple of BK, so a k-contiguous operand needs a per-lane
+    // guard in its last slab (an r-contiguous one never does: the descriptor's range is that guard).
+    template <bool KG>
+    __device__ static __forceinline__ void issue_one(const Plan& pl, u32x4_t ds, int k0, int k_lim, uint32_t lds_base, int i) {
         const uint32_t wave_base = lds_base + (threadIdx.x >> 6) * 1024;
-        uint32_t off = pl.voff[i] + kstep;
-        if (KC) off = pl.kcol[i] + k0 < k_lim ? off : OOB_OFFSET;
+        uint32_t off = pl.voff[i];
+        if (KC && KG) off = pl.kcol[i] + k0 < k_lim ? off : OOB_OFFSET;
         load_to_lds(ds, off, __builtin_amdgcn_readfirstlane(wave_base + i * NT * 16));
     }
     // LDS -> MFMA operand for the 32 tile rows rbase..rbase+31 (this lane: row
@@ -424,7 +429,7 @@ struct TileWalk {
 // them as one stream through the LDS ring, so the first slabs of the next tile
 // are already resident when the epilogue of the current one ends, and no
 // workgroup launch or cold first load sits between two tiles.
-template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT, int NWN>
+template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT, int NWN, bool KG>
 __device__ __forceinline__ void gemm_body(const GemmArgs& p) {
     typedef GemmSmem<T, BM, BN, BK, A_KC, B_KC, NWN> SM;
     typedef typename SM::TA TA;
@@ -487,19 +492,20 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p) {
         pk0 = p_more ? p_kt * BK : 0;
         pkl = p_more ? pw.k_lim : 0;              // k_lim 0: every guard fails, nothing is read
         if (!p_more) { dsA[2] = 0; dsB[2] = 0; }  // empty range: every load returns zeros
+        const u32x4_t sdA = TA::slab_desc(dsA, TA::slab_shift(p.lda, pk0)), sdB = TB::slab_desc(dsB, TB::slab_shift(p.ldb, pk0));
         // the descriptors are wave-uniform by construction; say so to the compiler
         // (they must sit in scalar registers for the load instruction)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            pua[i] = __builtin_amdgcn_readfirstlane(dsA[i]);
-            pub[i] = __builtin_amdgcn_readfirstlane(dsB[i]);
+            pua[i] = __builtin_amdgcn_readfirstlane(sdA[i]);
+            pub[i] = __builtin_amdgcn_readfirstlane(sdB[i]);
         }
         plds = lds0 + st * SM::STAGE;
         ++p_kt;
     };
     auto produce_issue = [&](int i) {   // load i of the prepared slab (i < SM::LOADS; A's loads come first)
-        if (i < TA::PER_THREAD) TA::issue_one(planA, pua, p.lda, pk0, pkl, plds, i);
-        else TB::issue_one(planB, pub, p.ldb, pk0, pkl, plds + TA::BYTES, i - TA::PER_THREAD);
+        if (i < TA::PER_THREAD) TA::template issue_one<KG>(planA, pua, pk0, pkl, plds, i);
+        else TB::template issue_one<KG>(planB, pub, pk0, pkl, plds + TA::BYTES, i - TA::PER_THREAD);
     };
     auto produce = [&](int st) {
         produce_prepare(st);
@@ -804,9 +810,9 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& p) {
     wait_vmcnt<0>();
 }
 
-template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT, int NWN>
+template <typename T, int BM, int BN, int BK, bool A_KC, bool B_KC, int EPI, int ACT, int NWN, bool KG>
 __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmArgs p) {   // two waves per SIMD: at most 256 registers
-    gemm_body<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN>(p);
+    gemm_body<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN, KG>(p);
 }
 
 // Two independent grouped GEMMs in one launch: every workgroup walks its tiles of the
@@ -814,11 +820,11 @@ __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_kernel(const GemmAr
 // two products must not depend on each other), so a workgroup that is done with the first
 // starts the second at once: one launch, one ramp-up and one tail instead of two, and the
 // workgroups drift apart, which spreads the store bursts of their epilogues.
-template <typename T, int BM, int BN, int BK, bool A1, bool B1, int EPI1, bool A2, bool B2, int EPI2, int NWN>
+template <typename T, int BM, int BN, int BK, bool A1, bool B1, int EPI1, bool A2, bool B2, int EPI2, int NWN, bool KG>
 __global__ __launch_bounds__(128 * NWN, 2) void grouped_gemm_pair_kernel(const GemmArgs p1, const GemmArgs p2) {
-    gemm_body<T, BM, BN, BK, A1, B1, EPI1, 0, NWN>(p1);
+    gemm_body<T, BM, BN, BK, A1, B1, EPI1, 0, NWN, KG>(p1);
     __syncthreads();      // every wave is done with the ring and the tile table of the first product
-    gemm_body<T, BM, BN, BK, A2, B2, EPI2, 0, NWN>(p2);
+    gemm_body<T, BM, BN, BK, A2, B2, EPI2, 0, NWN, KG>(p2);
 }
 
 // Number of compute units of the current device (looked up once per device).
@@ -871,10 +877,19 @@ static bool launch_gemm(GemmArgs p, int E, hipStream_t st) {
     p.tiles_n = ceil_div(p.N, BN);
     p.E = E;
     const size_t smem = SM::BYTES + WALK_BYTES;
-    auto kern = grouped_gemm_kernel<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN>;
-    static unsigned long long opted = 0;
-    if (!lds_opt_in((const void*)kern, smem, &opted)) return false;
-    kern<<<gemm_grid((long long)E * p.tiles_m * p.tiles_n), SM::NT, smem, st>>>(p);
+    const int grid = gemm_grid((long long)E * p.tiles_m * p.tiles_n);
+    // a k-contiguous operand whose reduction length is not a multiple of BK needs the guarded instance
+    const bool kg = (A_KC || B_KC) && !p.var_k && p.K % BK != 0;
+    static unsigned long long opted[2] = {0, 0};
+    if (kg) {
+        auto kern = grouped_gemm_kernel<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN, true>;
+        if (!lds_opt_in((const void*)kern, smem, &opted[1])) return false;
+        kern<<<grid, SM::NT, smem, st>>>(p);
+    } else {
+        auto kern = grouped_gemm_kernel<T, BM, BN, BK, A_KC, B_KC, EPI, ACT, NWN, false>;
+        if (!lds_opt_in((const void*)kern, smem, &opted[0])) return false;
+        kern<<<grid, SM::NT, smem, st>>>(p);
+    }
     return true;
 }
 
@@ -887,11 +902,19 @@ static bool launch_gemm_pair(GemmArgs p1, GemmArgs p2, int E, hipStream_t st) {
     p1.tiles_m = ceil_div(p1.M, BM); p1.tiles_n = ceil_div(p1.N, BN); p1.E = E;
     p2.tiles_m = ceil_div(p2.M, BM); p2.tiles_n = ceil_div(p2.N, BN); p2.E = E;
     const size_t smem = (SM1::BYTES > SM2::BYTES ? SM1::BYTES : SM2::BYTES) + WALK_BYTES;
-    auto kern = grouped_gemm_pair_kernel<T, BM, BN, BK, A1, B1, EPI1, A2, B2, EPI2, NWN>;
-    static unsigned long long opted = 0;
-    if (!lds_opt_in((const void*)kern, smem, &opted)) return false;
     const long long t1 = (long long)E * p1.tiles_m * p1.tiles_n, t2 = (long long)E * p2.tiles_m * p2.tiles_n;
-    kern<<<gemm_grid(t1 > t2 ? t1 : t2), SM1::NT, smem, st>>>(p1, p2);
+    const int grid = gemm_grid(t1 > t2 ? t1 : t2);
+    const bool kg = ((A1 || B1) && !p1.var_k && p1.K % BK != 0) || ((A2 || B2) && !p2.var_k && p2.K % BK != 0);
+    static unsigned long long opted[2] = {0, 0};
+    if (kg) {
+        auto kern = grouped_gemm_pair_kernel<T, BM, BN, BK, A1, B1, EPI1, A2, B2, EPI2, NWN, true>;
+        if (!lds_opt_in((const void*)kern, smem, &opted[1])) return false;
+        kern<<<grid, SM1::NT, smem, st>>>(p1, p2);
+    } else {
+        auto kern = grouped_gemm_pair_kernel<T, BM, BN, BK, A1, B1, EPI1, A2, B2, EPI2, NWN, false>;
+        if (!lds_opt_in((const void*)kern, smem, &opted[0])) return false;
+        kern<<<grid, SM1::NT, smem, st>>>(p1, p2);
+    }
     return true;
 }
 
