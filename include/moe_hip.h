@@ -47,6 +47,11 @@
  *    x[T, d_model]; stream 2 = expert dropout, indexed over h[E, C, d_ff].
  *  - Shape limits: T, d_model, d_ff, E, capacity >= 1; k in {1,2}; E >= k;
  *    E <= 256; d_model and d_ff multiples of 8; T*k and E*capacity < 2^30.
+ *    The expert FFN entry points address one expert's slice of a tensor with
+ *    32-bit byte offsets and also need (capacity + 512) * max(d_model, d_ff) * 4
+ *    < 2^31 and d_model * d_ff * 4 < 2^31 (else MOE_ERR_SHAPE).
+ *  - One GPU per call: the device that is current when an entry point is called
+ *    must be the one that owns the buffers and the stream.
  */
 #ifndef MOE_HIP_H
 #define MOE_HIP_H
@@ -216,14 +221,19 @@ int moe_expert_ffn_fwd_dropout(const moe_shape* shape, const void* xd, const int
 int moe_combine_fwd(const moe_shape* shape, const void* yd, const int32_t* expert_idx,
                     const int32_t* slot, const float* gate_w_or_null, void* y, void* stream);
 
-/* Combine, backward.  For kept (t,j), with e = expert_idx[t,j], s = slot[t,j]:
+/* Combine, backward: the derivative of the gate-weighted mixture above (the
+ * combine of Sec. 3.1 / Sec. 5.1) with respect to the expert outputs and the
+ * gate weights.  For kept (t,j), with e = expert_idx[t,j], s = slot[t,j]:
  *   dyd[e,s,:]   = gate_w[t,j] * dy[t,:]
  *   dgate_w[t,j] = <dy[t,:], yd[e,s,:]>          (0 for a dropped choice) */
 int moe_combine_bwd(const moe_shape* shape, const void* dy, const void* yd,
                     const int32_t* expert_idx, const int32_t* slot, const float* gate_w,
                     void* dyd, float* dgate_w, void* stream);
 
-/* Expert feed-forward block, backward.  Per expert, over its first n_e rows:
+/* Expert feed-forward block, backward: the derivative of the two-matmul expert
+ * of Sec. 4.2 (moe_expert_ffn_fwd) with respect to its input rows and its two
+ * weight matrices; like the forward, this is where the layer's compute sits
+ * (Sec. 2.3).  Per expert, over its first n_e rows:
  *   dh = dyd * W2^T,  dz = dh .* dact_saved,  dW2 = h_saved^T * dyd,
  *   dxd = dz * W1^T,  dW1 = xd^T * dz.
  * dW1[E,d_model,d_ff] and dW2[E,d_ff,d_model] are float; an expert with no
@@ -233,7 +243,9 @@ int moe_expert_ffn_bwd(const moe_shape* shape, const void* dyd, const void* xd,
                        const void* W1, const void* W2, void* dxd, float* dW1, float* dW2,
                        void* ws, size_t ws_bytes, void* stream);
 
-/* Gate, backward (selection and slots are constants):  with dg_j = dgate_w[t,j]
+/* Gate, backward: the derivative of the top-1 / top-2 gate weights of Sec. 5.1
+ * (moe_gate_route) through the softmax with respect to the logits; the
+ * selection and the capacity slots (Sec. 3.1) are constants.  With dg_j = dgate_w[t,j]
  * for kept choices and 0 for dropped ones,
  *   k=1: dp[t,e0] = dg_0
  *   k=2: S = p[t,e0]+p[t,e1]; dp[t,e0] = p[t,e1](dg_0-dg_1)/S^2; dp[t,e1] = p[t,e0](dg_1-dg_0)/S^2
@@ -261,7 +273,8 @@ int moe_gate_bwd_aux(const moe_shape* shape, const float* dgate_w, const float* 
                      const int32_t* expert_idx, const int32_t* slot, const float* first_frac,
                      float aux_coef, float* dlogits, void* stream);
 
-/* Gate projection, backward:
+/* Gate projection, backward: the derivative of the gating matrix product of
+ * Sec. 3.2 (moe_gate_logits) with respect to the gate matrix and the tokens:
  *   dWg[d_model,E]  = x^T * dlogits                       (overwritten)
  *   dx_accum[T,d]  += dlogits * Wg^T                      (ACCUMULATED into the
  *   caller's dx, which already holds dispatch's backward; pass NULL to skip).
@@ -290,15 +303,6 @@ int moe_dispatch_gate_logits_bwd(const moe_shape* shape, const void* x, const fl
                                  const float* dlogits, const void* dxd, const int32_t* expert_idx,
                                  const int32_t* slot, float jitter_eps, uint64_t seed, float* dWg,
                                  void* dx, void* ws, size_t ws_bytes, void* stream);
-
-/* Measurement aid, not a step of the layer (for benchmarks that print what the
- * chip sustains beside the published peak): n_workgroups x 4 waves each issue
- * iters x 8 independent v_mfma_f32_32x32x16_bf16 on register-resident operands
- * (random_operands != 0: seeded pseudo-random values, else all-equal ones).
- * Work = n_workgroups * 4 * iters * 8 * 32768 flop; the caller times it.
- * out: n_workgroups * 256 floats, written once so that the loop is not dead code. */
-int moe_microbench_mfma_bf16(int32_t n_workgroups, int32_t iters, int32_t random_operands, float* out,
-                             void* stream);
 
 #ifdef __cplusplus
 }

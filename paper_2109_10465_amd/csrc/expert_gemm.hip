@@ -14,31 +14,41 @@
 // either k-contiguous in memory (KC) or r-contiguous (!KC); no transposed copy
 // of any tensor is ever materialised.
 //
-// Structure of a workgroup (bf16: 8 waves, 2 x 4, two per SIMD so that one wave's
-// LDS waits and epilogue math hide behind the other's MFMAs; fp32: 4 waves, 2 x 2;
+// Structure of a workgroup (bf16: 8 waves, 2 x 4, two per SIMD; fp32: 4 waves, 2 x 2;
 // one persistent workgroup per CU):
-//   * walks BM x BN output tiles; workgroup w serves XCD w % 8 and that XCD's
-//     contiguous run of tiles (= whole experts), so co-resident tiles share
-//     operand panels in the XCD's L2; the slabs of all its tiles form one stream
-//     through the LDS ring, i.e. the next tile's first slabs arrive under the
-//     current tile's epilogue;
-//   * streams BK-deep slabs of both operands with 16-byte buffer loads that
-//     write straight into LDS (no register staging), NSTAGE-1 slabs ahead of
-//     the one being multiplied.  A stage is refilled as soon as the fragments
-//     of its last k-step sit in registers, i.e. one full slab period before
-//     the slab is needed (bf16: BK = 64, so a K-contiguous operand is fetched
-//     in 128-byte row pieces, two 64 KB stages); the buffer range check
-//     supplies the zero fill for rows
-//     >= n_e (no branches in the loop); LDS tiles are unpadded and XOR-swizzled
-//     in 16-byte units so that fragment reads are bank-conflict free;
+//   * walks BM x BN output tiles.  Only tiles that hold rows exist; the expert-major
+//     tile sequence is dealt block-cyclically, a block of as many consecutive tiles
+//     as an XCD has workgroups going to one XCD (workgroup w runs on XCD w % 8), so
+//     the tiles an XCD works on at one time are neighbours and share operand panels
+//     in its L2, every workgroup gets the same number of tiles up to one, and a
+//     heavily loaded expert is spread over all XCDs.  The slabs of all tiles of a
+//     workgroup form one stream through the LDS ring: the next tile's first slabs
+//     arrive under the current tile's epilogue;
+//   * streams BK-deep slabs of both operands with 16-byte buffer loads that write
+//     straight into LDS (no register staging).  bf16: BK = 64 (a k-contiguous operand
+//     is fetched in 128-byte row pieces), two 64 KB stages.  The B half of a stage is
+//     released early: a wave holds few B fragments, so it reads those of all four
+//     k-steps during the slab's first step and the half is refilled three k-steps
+//     before the A half - requests are in flight nearly all the time instead of in
+//     one burst per slab, and B has 1.75 slab periods to arrive.  The slab's offset
+//     is applied to the buffer descriptor (scalar work); the descriptor's range check
+//     supplies the zero fill for rows >= n_e, so the loop has no branches.  LDS tiles
+//     are unpadded and XOR-swizzled in 16-byte units (fragment reads are free of bank
+//     conflicts);
 //   * each wave accumulates (BM/2) x (BN/NWN) in 32x32 MFMA tiles
 //     (bf16: v_mfma_f32_32x32x16_bf16, fp32: v_mfma_f32_32x32x2_f32); !KC bf16
-//     operands are read from LDS with the transposing ds_read_b64_tr_b16;
+//     operands are read from LDS with the transposing ds_read_b64_tr_b16.  A wave
+//     issues strictly in order and an MFMA holds it for the MFMA's 32 cycles, so the
+//     matrix pipe is kept busy by the SIMD's other wave; loads and fragment reads are
+//     dealt evenly over the MFMA slots for that reason;
 //   * the epilogue passes the accumulators through LDS so that every global
 //     store is a full 8/16-byte vector along the row; the activation and its
 //     derivative are evaluated once, in the forward epilogue (code kept in a
 //     rolled loop), and the backward epilogue only multiplies by the saved
-//     derivative, which it fetched into registers before the main loop.
+//     derivative, which it fetched into registers before the main loop;
+//   * the backward's four products run as two launches of two independent products
+//     each (dz with dW2, dxd with dW1): a workgroup walks its tiles of the first,
+//     then of the second.
 #include <math.h>
 #include "moe_common.h"
 

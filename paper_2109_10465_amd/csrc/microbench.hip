@@ -2,6 +2,7 @@
 // register-resident operands, so that a benchmark can print what this chip
 // sustains next to the published peak the roofline is quoted against.
 #include "moe_common.h"
+#include "../../include/moe_bench_aid.h"
 
 typedef float mb_f32x16 __attribute__((ext_vector_type(16)));
 

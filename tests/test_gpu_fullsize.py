@@ -1,7 +1,8 @@
 """GPU parity at the full workload sizes, in the launch configuration the
-benchmark times.  cfg3 and cfg4 are small enough for the whole oracle; cfg5 is
-checked on sampled tokens, rows and weight-gradient columns that the oracle
-computes one by one (plus full routing, which is bit-exact)."""
+benchmark times.  cfg3, cfg4 and cfg5 are checked on sampled tokens, rows and
+weight-gradient columns that the oracle computes one by one, plus the routing
+in full (bit-exact); cfg3 is small enough to be compared, in addition, with the
+whole oracle, every element."""
 import time
 
 import numpy as np
