@@ -106,7 +106,7 @@ def main():
         ("gate_route", lambda: B.moe_gate_route_grouped(s, args.groups, L.logits, keys, L.probs, L.expert_idx,
                                                         L.gate_w, L.slot, L.expert_count, L.expert_demand,
                                                         L.slot_src, L.ws)),
-        ("dispatch", lambda: B.moe_dispatch(s, x, L.slot_src, L.expert_count, L.xd)),
+        ("dispatch", lambda: B.moe_dispatch_tokens(s, x, L.expert_idx, L.slot, L.xd)),
         ("expert_ffn_fwd", (lambda: B.moe_expert_ffn_fwd_dropout(s, L.xd, L.expert_count, W1, W2, args.drop_p, 7,
                                                                  L.h, L.dact, L.yd))
          if args.drop_p > 0 else
@@ -202,7 +202,7 @@ def main():
     alg = {
         "gate_logits": Tn * dm * sb + dm * E * 4 + Tn * E * 4,
         "gate_route": Tn * E * 4 * 2 + 12 * Tn * k + 4 * Tn + 4 * Tn * k + 4 * E * C + 8 * E,
-        "dispatch": kept_tok * dm * sb + 4 * E * C + M * dm * sb,
+        "dispatch": kept_tok * dm * sb + 8 * Tn * k + M * dm * sb,
         "combine_fwd": M * dm * sb + 12 * Tn * k + Tn * dm * sb,
         "combine_bwd": Tn * dm * sb + M * dm * sb + M * dm * sb + 4 * Tn * k,
         "gate_bwd": Tn * E * 4 * 2 + 16 * Tn * k,

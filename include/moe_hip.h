@@ -176,6 +176,14 @@ int moe_gate_route_static(const moe_shape* shape, const float* logits, const flo
 int moe_dispatch(const moe_shape* shape, const void* x, const int32_t* slot_src,
                  const int32_t* expert_count, void* xd, void* stream);
 
+/* The same dispatch (Sec. 3.1), addressed from the token side: every token row
+ * x[t,:] is read once and written to the slot of each of its kept choices,
+ *   xd[expert_idx[t,j], slot[t,j], :] = x[t,:]   for slot[t,j] >= 0,
+ * instead of once per kept choice.  Same result as moe_dispatch, bit for bit,
+ * for a slot / slot_src pair that comes from one routing call. */
+int moe_dispatch_tokens(const moe_shape* shape, const void* x, const int32_t* expert_idx,
+                        const int32_t* slot, void* xd, void* stream);
+
 /* Expert feed-forward block, forward (Sec. 4.2: d_model -> d_ff -> d_model;
  * Sec. 2.3: the per-expert matmuls carry the compute).  For every expert e and
  * its first n_e = expert_count[e] rows:

@@ -21,7 +21,7 @@ EXPORTS = [
     "moe_utilisation_accumulate", "moe_gate_route_grouped",
     "moe_gate_logits_jitter", "moe_gate_logits_bwd_jitter", "moe_expert_ffn_fwd_dropout",
     "moe_dispatch_gate_logits_bwd", "moe_microbench_mfma_bf16",
-    "moe_gate_route_static", "moe_gate_route_static_max_bytes",
+    "moe_gate_route_static", "moe_gate_route_static_max_bytes", "moe_dispatch_tokens",
 ]
 
 
@@ -62,6 +62,7 @@ def lib():
             "moe_gate_logits": [shp] + [vp] * 5,
             "moe_gate_route": [shp] + [vp] * 10 + [sz, vp],
             "moe_dispatch": [shp] + [vp] * 5,
+            "moe_dispatch_tokens": [shp] + [vp] * 5,
             "moe_expert_ffn_fwd": [shp] + [vp] * 8,
             "moe_combine_fwd": [shp] + [vp] * 6,
             "moe_combine_bwd": [shp] + [vp] * 8,
@@ -155,6 +156,11 @@ def moe_gate_route_grouped(shape, n_groups, logits, rts_keys, probs, expert_idx,
 def moe_dispatch(shape, x, slot_src, expert_count, xd, stream=None):
     _check(lib().moe_dispatch(ctypes.byref(shape), _p(x), _p(slot_src), _p(expert_count), _p(xd),
                               _stream(stream)), "moe_dispatch")
+
+
+def moe_dispatch_tokens(shape, x, expert_idx, slot, xd, stream=None):
+    _check(lib().moe_dispatch_tokens(ctypes.byref(shape), _p(x), _p(expert_idx), _p(slot), _p(xd),
+                                     _stream(stream)), "moe_dispatch_tokens")
 
 
 def moe_expert_ffn_fwd(shape, xd, expert_count, W1, W2, h_saved, dact_saved, yd, stream=None):

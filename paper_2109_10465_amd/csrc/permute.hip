@@ -31,6 +31,35 @@ __global__ __launch_bounds__(64 * ROWS_PER_WG) void dispatch_kernel(int d, int k
     for (int v = lane; v < nvec; v += 64) dst[v] = src[v];
 }
 
+// The same copy, token-major: one wave per token reads x[t,:] once and writes it to the
+// slot of each kept choice (the slot-major kernel above reads a token's row once per
+// kept choice).  xd[expert_idx[t,j], slot[t,j], :] = x[t,:] for slot[t,j] >= 0.
+template <typename T>
+__global__ __launch_bounds__(64 * ROWS_PER_WG) void dispatch_tokens_kernel(int Tn, int d, int k, int E, int C,
+                                                                           const T* __restrict__ x,
+                                                                           const int32_t* __restrict__ expert_idx,
+                                                                           const int32_t* __restrict__ slot,
+                                                                           T* __restrict__ xd) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * ROWS_PER_WG + (threadIdx.x >> 6);
+    if (t >= Tn) return;
+    uint4* dst[2] = {nullptr, nullptr};
+    for (int j = 0; j < k; ++j) {
+        const int s = slot[(size_t)t * k + j];
+        const int e = expert_idx[(size_t)t * k + j];
+        // ids and slots come from the routing call; anything else is skipped, never dereferenced
+        if (s >= 0 && s < C && (unsigned)e < (unsigned)E) dst[j] = reinterpret_cast<uint4*>(xd + ((size_t)e * C + s) * d);
+    }
+    if (!dst[0] && !dst[1]) return;      // fully dropped token: nothing to copy, x[t] is not read
+    const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)t * d);
+    const int nvec = d * (int)sizeof(T) / 16;
+    for (int v = lane; v < nvec; v += 64) {
+        const uint4 q = src[v];
+        if (dst[0]) dst[0][v] = q;
+        if (dst[1]) dst[1][v] = q;
+    }
+}
+
 // y[t,:] = sum_j [slot>=0] g_j * yd[e_j, slot_j, :]
 template <typename T>
 __global__ __launch_bounds__(64 * ROWS_PER_WG) void combine_fwd_kernel(int Tn, int d, int k, int C,
@@ -135,6 +164,22 @@ extern "C" int moe_dispatch(const moe_shape* shape, const void* x, const int32_t
     else
         dispatch_kernel<float><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->d_model, shape->k, shape->capacity, n_rows, shape->T * shape->k,
                                                      (const float*)x, slot_src, expert_count, (float*)xd);
+    return launch_status();
+}
+
+extern "C" int moe_dispatch_tokens(const moe_shape* shape, const void* x, const int32_t* expert_idx,
+                                   const int32_t* slot, void* xd, void* stream) {
+    int rc = check_shape(shape);
+    if (rc) return rc;
+    if (!x || !expert_idx || !slot || !xd) return MOE_ERR_NULL;
+    const int grid = ceil_div(shape->T, ROWS_PER_WG);
+    hipStream_t st = (hipStream_t)stream;
+    if (shape->dtype == MOE_BF16)
+        dispatch_tokens_kernel<bf16_t><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->T, shape->d_model, shape->k, shape->E, shape->capacity,
+                                                                 (const bf16_t*)x, expert_idx, slot, (bf16_t*)xd);
+    else
+        dispatch_tokens_kernel<float><<<grid, 64 * ROWS_PER_WG, 0, st>>>(shape->T, shape->d_model, shape->k, shape->E, shape->capacity,
+                                                                (const float*)x, expert_idx, slot, (float*)xd);
     return launch_status();
 }
 

@@ -88,7 +88,7 @@ class MoELayer:
         if self.aux_coef != 0.0:
             B.moe_aux_loss(s, self.probs, self.expert_idx, self.first_frac, self.mean_prob, self.aux_loss,
                            self.ws)
-        B.moe_dispatch(s, x, self.slot_src, self.expert_count, self.xd)
+        B.moe_dispatch_tokens(s, x, self.expert_idx, self.slot, self.xd)    # reads every token row once
         if self.drop_p > 0.0:
             B.moe_expert_ffn_fwd_dropout(s, self.xd, self.expert_count, W1, W2, self.drop_p, self.seed, self.h,
                                          self.dact, self.yd)

@@ -118,6 +118,30 @@ def test_combine_of_dispatch_with_unit_weights_is_identity_on_kept_tokens():
     assert np.array_equal(back, nkept[:, None] * d["x"])
 
 
+@pytest.mark.parametrize("dtype,k", [(I.BF16, 2), (I.F32, 1)])
+def test_dispatch_from_the_slot_side_and_from_the_token_side_agree(dtype, k):
+    """moe_dispatch (one wave per slot, source looked up in slot_src) and moe_dispatch_tokens (one wave per
+    token, destinations from expert_idx / slot) fill the rows in use with the same bit copies of x; neither
+    touches a row that is not in use."""
+    w = I.small("dispatch2", 1500, 72, 64, 7, k, 430 if k == 2 else 260, dtype, skew="hot0", skew_param=0.5)   # some experts overflow, others underfill
+    d = I.make_inputs(w, seed=23)
+    d["Wg"] = d["Wg"] * 8.0
+    layer, got = G.run_layer(w, d)
+    x = G.to_dev(d["x"], w.dtype)
+    fill = 7.0
+    a = torch.full_like(layer.xd, fill)
+    b = torch.full_like(layer.xd, fill)
+    B.moe_dispatch(layer.shape, x, layer.slot_src, layer.expert_count, a)
+    B.moe_dispatch_tokens(layer.shape, x, layer.expert_idx, layer.slot, b)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    a = G.host(a)
+    m = G.row_mask(got["expert_count"], w.capacity)
+    assert (got["slot"] < 0).any() and m.any() and not m.all()
+    assert np.array_equal(a[m], d["x"][got["slot_src"][m] // w.k])
+    assert np.all(a[~m] == fill)
+
+
 def test_two_runs_are_bit_identical():
     w = I.small("determinism", 2000, 128, 256, 8, 2, 450, I.BF16)
     d = I.make_inputs(w, seed=19)
