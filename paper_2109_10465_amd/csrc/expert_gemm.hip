@@ -364,6 +364,7 @@ struct GemmSmem {
 // every workgroup gets the same number of tiles up to one; and the tiles of a
 // heavily loaded expert (long reductions in the weight-gradient GEMMs) are spread
 // over all workgroups instead of piling up on one XCD.
+#define WALK_BAND 4                     // row tiles per band of the walk inside an expert
 #define WALK_SLOTS 257                  // experts + 1
 #define WALK_BYTES (WALK_SLOTS * 4 + 12)
 template <int BM, int BN>
@@ -423,10 +424,19 @@ struct TileWalk {
         const int count = __builtin_amdgcn_readfirstlane(tp[e + 1]) - first;
         const int rem = t - first;
         const int tm_e = count / p.tiles_n;   // row tiles of this expert
-        // inside an expert the dimension with fewer tiles varies fastest
+        // Inside an expert the tiles are taken band by band: a band is WALK_BAND row tiles high
+        // and all column tiles wide, and inside it the row tile varies fastest.  A run of 32
+        // consecutive tiles (what one XCD works on at a time) is then a 4 x 8 block that shares
+        // 4 + 8 operand panels in the XCD's L2, whatever the expert's size (one row tile per
+        // column tile, or the reverse, would fetch 32 + 1 panels for the same 32 tiles).
         int tm, tn;
-        if (tm_e <= p.tiles_n) { tn = rem / tm_e; tm = rem - tn * tm_e; }
-        else { tm = rem / p.tiles_n; tn = rem - tm * p.tiles_n; }
+        {
+            const int band = rem / (WALK_BAND * p.tiles_n);
+            const int r = rem - band * WALK_BAND * p.tiles_n;
+            const int rows = min(WALK_BAND, tm_e - band * WALK_BAND);   // the last band may be lower
+            tn = r / rows;
+            tm = band * WALK_BAND + (r - tn * rows);
+        }
         const int n_e = max(0, min(p.expert_count[e], p.var_k ? p.K : p.M));
         m0 = tm * BM; n0 = tn * BN;
         m_lim = p.var_k ? p.M : n_e;
