@@ -106,40 +106,7 @@ template <> struct Mma<float> {
     }
 };
 
-// Raw buffer descriptor (4 SGPRs) over `bytes` bytes at p: loads beyond the
-// range return 0 (and, for loads into LDS, store 0).
-__device__ __forceinline__ u32x4_t make_desc(const void* p, uint32_t bytes) {
-    const uint64_t a = (uint64_t)p;
-    u32x4_t d;
-    d[0] = (uint32_t)a;
-    d[1] = (uint32_t)(a >> 32) & 0xffffu;
-    d[2] = bytes;
-    d[3] = 0x00020000u;
-    return d;
-}
 #define OOB_OFFSET 0x80000000u  // beyond any descriptor this kernel builds (slices < 2 GiB)
-
-// One wavefront-wide 16-byte-per-lane load from a raw buffer straight into LDS:
-// lane l's 16 bytes land at LDS byte address lds_base + 16*l (lds_base is wave
-// uniform and travels in M0).  Written as asm so that the compiler does not
-// serialise every later LDS read behind the load; completion is tracked by
-// hand with vmcnt (see the main loop).  M0 is a reserved register for the
-// compiler: it never keeps a value live in it across other code but writes it
-// immediately before each instruction of its own that reads it, so overwriting
-// it here is safe (naming it as a clobber is rejected as "reserved").
-__device__ __forceinline__ void load_to_lds(u32x4_t desc, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_base), "v"(voff), "s"(desc) : "memory");
-}
-// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in 15:14)
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4) | (0xf << 8));
-}
-
-// the same, and every LDS operation of this wave has completed as well
-template <int N> __device__ __forceinline__ void wait_vmcnt_lgkm0() {
-    __builtin_amdgcn_s_waitcnt((N & 0xf) | ((N >> 4) << 14) | (0x7 << 4));
-}
 
 // LDS tile of one operand: BR rows (r) x BK reduction entries, unpadded, as
 // 16-byte slots; slot p is filled by thread p % NT in its (p / NT)-th load.

@@ -137,9 +137,265 @@ __global__ __launch_bounds__(64 * GLM_KSPLIT, NB == 1 ? 4 : 2) void gate_logits_
         }
 }
 
+// ---------------------------------------------------------------------------
+// The same product for bf16 activations and 33..128 experts (E % 4 == 0, no
+// jitter), tiled like a GEMM: with that many experts the gate matrix (d x E fp32)
+// is the larger operand of a token tile, and splitting it into bf16 parts costs
+// about as much vector-ALU time as the product costs matrix-pipe time, so both must
+// be done once per workgroup, not once per wave or per 32 tokens, and side by side.
+// Workgroup: 32*TT tokens x all experts, reduction in 64-deep slabs through a
+// two-stage LDS ring, 12 waves in two roles (two producers and one consumer per SIMD,
+// so the splitting of one slab runs under the MFMAs of the previous one):
+//   producers (waves 0-7) move a slab global -> registers -> LDS.  x: rows of 128
+//       bytes, 16-byte pieces XOR-swizzled so that a fragment read (32 rows x 16
+//       bytes) touches every bank once.  Wg: a thread loads rows 4kg..4kg+3 of expert
+//       quad 4q..4q+3 (16-byte loads, a wave instruction = two whole 512-byte rows),
+//       splits the 16 values exactly into three bf16 parts and writes them where
+//       the MFMA wants them: operand j (j = 0..3) stands for the experts 4r+j,
+//       r = tile column, so the four values of a load go to four operands and the
+//       four rows to four consecutive reduction entries of one lane: 8-byte LDS
+//       writes, contiguous over the wave; an operand is read back as 1 KB, 16
+//       bytes per lane.  The registers of two slabs are in flight (loads are
+//       issued two iterations before their values are used).
+//   consumers (waves 8-11) multiply: wave 8+j takes operand j over the whole slab
+//       for all TT token tiles (a B fragment serves TT MFMAs per part).
+// One barrier per slab.  At the end the tiles go through LDS and a thread stores
+// 4 consecutive experts of a token as 16 bytes.
+// ---------------------------------------------------------------------------
+#define GLL_BK 64
+#define GLL_PRODUCERS 512                 // threads in the producer role (8 waves)
+#define GLL_THREADS (GLL_PRODUCERS + 256) // + one consumer wave per SIMD
+#define GLL_LDO 132                       // floats per token row of the output stage
+template <int TT>
+struct GllSmem {
+    static constexpr int XB = TT * 32 * GLL_BK * 2;         // x slab
+    static constexpr int WB = 4 * (GLL_BK / 16) * 3 * 1024; // 4 operands x 4 steps x 3 parts x 1 KB
+    static constexpr int STAGE = XB + WB;
+    static constexpr int OUT = TT * 32 * GLL_LDO * 4;
+    static constexpr int BYTES = 2 * STAGE > OUT ? 2 * STAGE : OUT;
+};
+
+template <int TT>
+__global__ __launch_bounds__(GLL_THREADS, 1) void gate_logits_lds_kernel(
+    int Tn, int d, int E, const bf16_t* __restrict__ x, const float* __restrict__ Wg,
+    const float* __restrict__ bias, float* __restrict__ logits) {
+    typedef GllSmem<TT> SM;
+    extern __shared__ __align__(16) unsigned char gll_smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int t0 = blockIdx.x * 32 * TT;
+    const int rows_here = min(32 * TT, Tn - t0);
+    const int nslab = (d + GLL_BK - 1) / GLL_BK;
+    // every LDS operation of this wave is complete, then the workgroup meets; loads into
+    // registers stay in flight across it (a __syncthreads() would wait for them too)
+    auto lds_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+    glm_f32x16 acc[TT];
+    if (wave < GLL_PRODUCERS / 64) {
+        // descriptors in scalar registers for the hand-issued loads (ranges below 4 GiB by the shape limits)
+        u32x4_buf_t rs_x = make_desc(x + (size_t)t0 * d, (uint32_t)((size_t)rows_here * d * 2));
+        u32x4_buf_t rs_w = make_desc(Wg, (uint32_t)((size_t)d * E * 4));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            rs_x[i] = __builtin_amdgcn_readfirstlane(rs_x[i]);
+            rs_w[i] = __builtin_amdgcn_readfirstlane(rs_w[i]);
+        }
+        constexpr int XPT = TT * 32 * 8 / GLL_PRODUCERS;    // 16-byte pieces of x per thread and slab
+        struct Regs { u32x4_buf_t xr[XPT]; u32x4_buf_t wr[4]; };
+        // x: piece p = row*8 + c of the slab; LDS position of piece c in its row: c ^ ((row/2)%8)
+        uint32_t xoff[XPT], xdst[XPT];
+        int xcol[XPT];
+#pragma unroll
+        for (int i = 0; i < XPT; ++i) {
+            const int p = threadIdx.x + i * GLL_PRODUCERS;
+            const int row = p >> 3, c = p & 7;
+            xoff[i] = (uint32_t)((row * d + c * 8) * 2);   // rows beyond T lie beyond the descriptor
+            xcol[i] = c * 8;
+            xdst[i] = (uint32_t)((row * 8 + (c ^ ((row >> 1) & 7))) * 16);
+        }
+        // Wg: this thread's quad of experts and its group of four rows of a slab
+        const int q = threadIdx.x & 31, kg0 = threadIdx.x >> 5;
+        const bool q_ok = 4 * q < E;                        // E % 4 == 0: a quad is inside or beyond
+        // The loads are issued by hand and their completion is awaited by hand (land): three
+        // slabs are in flight per thread, and the wait counts the compiler derives for loads
+        // that cross a loop's back edge drain all of them.  Every slab issues the same number
+        // of loads (slabs beyond d read zeros), so "two younger slabs" is a constant count.
+        constexpr int LOADS = 4 + XPT;
+        auto issue1 = [](u32x4_buf_t rs, uint32_t off) {
+            u32x4_buf_t v;
+            asm volatile("buffer_load_dwordx4 %0, %1, %2, 0 offen" : "=v"(v) : "v"(off), "s"(rs) : "memory");
+            return v;
+        };
+        // Workgroups start at different slabs and wrap around: in step they would all read the
+        // same 128-byte column of their rows, addresses a row pitch apart, i.e. a fraction of the
+        // memory channels at any one time.
+        const int rot = blockIdx.x % nslab;
+        auto load_slab = [&](int s, Regs& g) {
+            const int sr = s + rot - (s + rot >= nslab ? nslab : 0);
+            const int k0 = s < nslab ? sr * GLL_BK : d;     // slabs beyond the last read zeros
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = k0 + 4 * kg0 + i;
+                g.wr[i] = issue1(rs_w, (q_ok & (k < d)) ? (uint32_t)((k * E + 4 * q) * 4) : BUF_OOB);
+            }
+#pragma unroll
+            for (int i = 0; i < XPT; ++i)
+                g.xr[i] = issue1(rs_x, (xcol[i] + k0 < d) ? xoff[i] + (uint32_t)(k0 * 2) : BUF_OOB);
+        };
+        // waits until at most 2 * LOADS loads are outstanding: slab g has landed; the asm "modifies"
+        // the registers so that no use of them can be scheduled above it
+        auto land = [&](Regs& g) {
+            if constexpr (XPT == 2)
+                asm volatile("s_waitcnt vmcnt(%6)" : "+v"(g.wr[0]), "+v"(g.wr[1]), "+v"(g.wr[2]), "+v"(g.wr[3]),
+                             "+v"(g.xr[0]), "+v"(g.xr[XPT - 1]) : "n"(2 * LOADS) : "memory");
+            else
+                asm volatile("s_waitcnt vmcnt(%5)" : "+v"(g.wr[0]), "+v"(g.wr[1]), "+v"(g.wr[2]), "+v"(g.wr[3]),
+                             "+v"(g.xr[0]) : "n"(2 * LOADS) : "memory");
+        };
+        // rows 4kg..4kg+3 are reduction entries 4*(kg%2) .. +3 of lane q + 32*((kg/2)%2) in step kg/4
+        const uint32_t wdst = (uint32_t)(((kg0 >> 2) * 3) * 1024 + (q + 32 * ((kg0 >> 1) & 1)) * 16 + (kg0 & 1) * 8);
+        auto store_slab = [&](const Regs& g, int stage) {
+            unsigned char* sx = gll_smem + stage * SM::STAGE;
+#pragma unroll
+            for (int i = 0; i < XPT; ++i) *reinterpret_cast<u32x4_buf_t*>(sx + xdst[i]) = g.xr[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t ph[4], pm[4], pl[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float w = __uint_as_float(g.wr[i][j]);
+                    ph[i] = __float_as_uint(w) & 0xffff0000u;
+                    const float w1 = w - __uint_as_float(ph[i]);
+                    pm[i] = __float_as_uint(w1) & 0xffff0000u;
+                    pl[i] = __float_as_uint(w1 - __uint_as_float(pm[i]));
+                }
+                unsigned char* dst = sx + SM::XB + wdst + j * (GLL_BK / 16) * 3 * 1024;
+                // the high halves of two words, the earlier reduction entry in the low half
+                constexpr uint32_t HH = 0x07060302u;
+                *reinterpret_cast<uint2*>(dst) =
+                    make_uint2(__builtin_amdgcn_perm(ph[1], ph[0], HH), __builtin_amdgcn_perm(ph[3], ph[2], HH));
+                *reinterpret_cast<uint2*>(dst + 1024) =
+                    make_uint2(__builtin_amdgcn_perm(pm[1], pm[0], HH), __builtin_amdgcn_perm(pm[3], pm[2], HH));
+                *reinterpret_cast<uint2*>(dst + 2048) =
+                    make_uint2(__builtin_amdgcn_perm(pl[1], pl[0], HH), __builtin_amdgcn_perm(pl[3], pl[2], HH));
+            }
+        };
+        static_assert(XPT == 1 || XPT == 2, "land() names every register of a slab");
+        Regs g0, g1, g2;
+        load_slab(0, g0);
+        load_slab(1, g1);
+        load_slab(2, g2);
+        land(g0);
+        store_slab(g0, 0);
+        load_slab(3, g0);
+        lds_barrier();                   // slab 0 is staged
+        // step n (the consumers multiply slab n): stage slab n+1, request slab n+4
+        auto step = [&](int n, Regs& g) {
+            land(g);
+            store_slab(g, (n + 1) & 1);  // that stage was last read before the previous barrier
+            load_slab(n + 4, g);
+            lds_barrier();
+        };
+        for (int s = 0;; s += 3) {
+            step(s, g1);
+            if (s + 1 >= nslab) break;
+            step(s + 1, g2);
+            if (s + 2 >= nslab) break;
+            step(s + 2, g0);
+            if (s + 3 >= nslab) break;
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may land in a register that is reused below
+    } else {
+        const int r = lane & 31, h = lane >> 5;
+        const int jw = wave - GLL_PRODUCERS / 64;
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tt][v] = 0.0f;
+        auto compute = [&](int stage) {
+            const unsigned char* sx = gll_smem + stage * SM::STAGE;
+            const unsigned char* sw = sx + SM::XB + jw * (GLL_BK / 16) * 3 * 1024 + lane * 16;
+#pragma unroll
+            for (int ks = 0; ks < GLL_BK / 16; ++ks) {
+                const bf16x8_hw_t w_hi = *reinterpret_cast<const bf16x8_hw_t*>(sw + (ks * 3 + 0) * 1024);
+                const bf16x8_hw_t w_mid = *reinterpret_cast<const bf16x8_hw_t*>(sw + (ks * 3 + 1) * 1024);
+                const bf16x8_hw_t w_lo = *reinterpret_cast<const bf16x8_hw_t*>(sw + (ks * 3 + 2) * 1024);
+                bf16x8_hw_t xa[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const int row = tt * 32 + r;
+                    xa[tt] = *reinterpret_cast<const bf16x8_hw_t*>(sx + (row * 8 + ((2 * ks + h) ^ ((row >> 1) & 7))) * 16);
+                }
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tt], w_lo, acc[tt], 0, 0, 0);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tt], w_mid, acc[tt], 0, 0, 0);
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tt], w_hi, acc[tt], 0, 0, 0);
+            }
+        };
+        lds_barrier();
+        for (int s = 0; s < nslab; s += 2) {
+            compute(0);
+            lds_barrier();
+            if (s + 1 >= nslab) break;
+            compute(1);
+            lds_barrier();
+        }
+        // accumulator element v of lane l: expert 4*(l%32) + jw, token row 8*(v/4) + 4*(l/32) + v%4
+        float* out = reinterpret_cast<float*>(gll_smem);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                out[(tt * 32 + 8 * (v >> 2) + 4 * h + (v & 3)) * GLL_LDO + 4 * r + jw] = acc[tt][v];
+    }
+    __syncthreads();
+    if (threadIdx.x < 512) {
+        const int q = threadIdx.x & 31, m0 = threadIdx.x >> 5;
+        const bool q_ok = 4 * q < E;
+        const float* o0 = reinterpret_cast<const float*>(gll_smem);
+        float4 b4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (bias && q_ok) b4 = *reinterpret_cast<const float4*>(bias + 4 * q);
+#pragma unroll
+        for (int i = 0; i < TT * 32 * 32 / 512; ++i) {
+            const int m = m0 + 16 * i;                      // token row; q = expert quad
+            const float4 a = *reinterpret_cast<const float4*>(o0 + m * GLL_LDO + 4 * q);
+            if (m < rows_here && q_ok)
+                *reinterpret_cast<float4*>(logits + (size_t)(t0 + m) * E + 4 * q) =
+                    make_float4(a.x + b4.x, a.y + b4.y, a.z + b4.z, a.w + b4.w);
+        }
+    }
+}
+
+template <int TT>
+static void launch_gate_logits_lds(const moe_shape* s, const void* x, const float* Wg, const float* bias,
+                                   float* logits, hipStream_t st) {
+    static unsigned long long opted = 0;     // bit per device: opt in to more than 64 KB of LDS
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev < 64 && !(opted >> dev & 1)) {
+        if (hipFuncSetAttribute((const void*)gate_logits_lds_kernel<TT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                GllSmem<TT>::BYTES) != hipSuccess) return;   // the launch below then fails and is reported
+        opted |= 1ull << dev;
+    }
+    gate_logits_lds_kernel<TT><<<ceil_div(s->T, 32 * TT), GLL_THREADS, GllSmem<TT>::BYTES, st>>>(
+        s->T, s->d_model, s->E, (const bf16_t*)x, Wg, bias, logits);
+}
+
 template <typename T>
 static void launch_gate_logits(const moe_shape* s, const void* x, const float* Wg, const float* bias,
                                float* logits, float eps, uint64_t seed, hipStream_t st) {
+    if constexpr (sizeof(T) == 2) {
+        // bias rows are read as 16 bytes: the pointer must be 16-byte aligned like every tensor here
+        if (eps == 0.0f && s->E > 32 && s->E <= 128 && s->E % 4 == 0 && ((uintptr_t)logits & 15) == 0 &&
+            ((uintptr_t)bias & 15) == 0 && ((uintptr_t)Wg & 15) == 0) {
+            // 128 tokens per workgroup when that still gives most compute units a workgroup
+            if (ceil_div(s->T, 128) >= 192) launch_gate_logits_lds<4>(s, x, Wg, bias, logits, st);
+            else launch_gate_logits_lds<2>(s, x, Wg, bias, logits, st);
+            return;
+        }
+    }
     // two token tiles per workgroup on the bf16 matrix path with more than 32 experts
 #define GLM(NB, JIT, TT) gate_logits_kernel<T, NB, JIT, TT><<<ceil_div(s->T, 32 * TT), 64 * GLM_KSPLIT, 0, st>>>( \
     s->T, s->d_model, s->E, (const T*)x, Wg, bias, logits, eps, seed)

@@ -155,6 +155,33 @@ def test_two_runs_are_bit_identical():
             assert np.array_equal(a[n], b[n]), n
 
 
+@pytest.mark.parametrize("T,d,E", [(1, 8, 36), (100, 72, 64), (129, 264, 100), (1000, 1024, 128), (5000, 200, 128),
+                                   (25000, 136, 44), (2049, 320, 33), (700, 64, 130), (300, 1032, 256)])
+@pytest.mark.parametrize("with_bias", [False, True])
+def test_gate_projection_with_many_experts(T, d, E, with_bias):
+    """bf16 activations and more than 32 experts: the projection is tiled like a GEMM (expert counts that are a
+    multiple of 4 up to 128) or runs per 32/64 tokens (the others).  Ragged token counts, reduction lengths that are
+    no multiple of the slab, one and several workgroups, both workgroup sizes; every logit against the oracle, per
+    row as well, and rows next to the output untouched."""
+    w = I.small("proj", T, d, 8, E, 1, 4, I.BF16, w_std=0.5)
+    data = I.make_inputs(w, seed=T + E)
+    if not with_bias:
+        data["bias"] = None
+    else:
+        data["bias"] = np.linspace(-1.0, 1.0, E).astype(np.float32)
+    ref64, _ = G.oracle_logits(dict(data, bias=data["bias"] if with_bias else np.zeros(E, np.float32)))
+    shape = B.make_shape(T, d, 8, E, 1, 4, I.BF16, 0)
+    lg = torch.full((T + 2, E), 7.0, device="cuda")
+    print(f"[gpu] projection T={T} d={d} E={E} bias={with_bias}", flush=True)
+    B.moe_gate_logits(shape, G.to_dev(data["x"], I.BF16), G.to_dev(data["Wg"], I.F32),
+                      G.to_dev(data["bias"], I.F32), lg[1:T + 1])
+    torch.cuda.synchronize()
+    got = G.host(lg)
+    assert (got[0] == 7.0).all() and (got[T + 1] == 7.0).all()
+    assert G.rel_l2(got[1:T + 1], ref64) <= 1e-5
+    G.assert_rows("logits", got[1:T + 1], ref64, 1e-5)
+
+
 def test_argument_errors_leave_outputs_untouched():
     w = I.small("err", 64, 16, 16, 4, 1, 16)
     s = B.make_shape(w.T, w.d_model, w.d_ff, w.E, w.k, w.capacity, w.dtype, w.act)

@@ -84,3 +84,17 @@ def test_argument_errors_are_reported_before_any_launch():
     assert "workspace" in B.moe_status_string(-4)
     with pytest.raises(B.MoeError):
         B._check(-2, "x")
+
+
+def test_build_rejects_scratch_in_kernels_with_hand_issued_loads():
+    """A kernel that issues loads through inline asm and waits for them by hand must not spill: the build reads the
+    compiler's resource-usage remarks and fails if such a kernel reports scratch memory."""
+    from paper_2109_10465_amd import build as bld
+    remark = ("gate.hip:1:1: remark: Function Name: _Z22gate_logits_lds_kernelILi4EEviiiPKtPKfS3_Pf [-Rpass-analysis]\n"
+              "gate.hip:1:1: remark:     VGPRs: 168 [-Rpass-analysis]\n"
+              "gate.hip:1:1: remark:     ScratchSize [bytes/lane]: {n} [-Rpass-analysis]\n")
+    bld.check_no_scratch("gate.hip", remark.format(n=0))
+    with pytest.raises(RuntimeError):
+        bld.check_no_scratch("gate.hip", remark.format(n=28))
+    # other kernels of the same file may spill
+    bld.check_no_scratch("gate.hip", remark.format(n=28).replace("gate_logits_lds_kernel", "gate_dx_kernel"))
