@@ -913,6 +913,212 @@ __global__ __launch_bounds__(64 * GDX_WAVES) void gate_dx_kernel(int Tn, int d, 
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same update for bf16 activations and 33..128 experts (E % 4 == 0, no
+// jitter).  With that many experts the 32-token kernel above reads and splits the
+// whole gate matrix once per 32 tokens, which costs several times the product
+// itself.  Here a workgroup owns 128 tokens: their dlogits rows are split once
+// (hi + lo) and stay in LDS as ready MFMA operands for the workgroup's lifetime;
+// each of the 8 waves then walks 64-column passes of d on its own, no barrier:
+// per 16 experts it loads its columns' gate rows (32 contiguous bytes per lane, the
+// B operand as it lies in memory), splits them once and uses them for all four
+// token tiles (12 MFMAs per split), so the vector ALU and the L2 see a quarter of
+// the work per token.  The tiles leave through the wave-private LDS stage as above.
+// ---------------------------------------------------------------------------
+#define GDW_KS 8                          // 16-expert steps held in LDS (E <= 128)
+template <int TT, int NW>                 // 32-token tiles and waves per workgroup
+struct GdwSmem {
+    static constexpr int A_BYTES = TT * GDW_KS * 2 * 1024;                // [tile][step][hi, lo] 1 KB operands
+    static constexpr int STAGE_LD = GDX_COLS + 4;
+    static constexpr int STAGE_BYTES = NW * 32 * STAGE_LD * 4;
+    static constexpr int ROW_BYTES = 2 * TT * 32 * 4;
+    static constexpr int BYTES = A_BYTES + STAGE_BYTES + ROW_BYTES;
+};
+
+template <int NSRC_G, int TT, int NW>   // NSRC_G: 0 = add to dx in place; 1, 2 = gather the token's k kept rows of dxd
+__global__ __launch_bounds__(64 * NW, TT == 2 ? 2 : 1) void gate_dx_wide_kernel(
+    int Tn, int d, int E, int k, int C, const float* __restrict__ dlogits, const float* __restrict__ Wg,
+    const bf16_t* __restrict__ dxd, const int32_t* __restrict__ expert_idx, const int32_t* __restrict__ slot,
+    bf16_t* __restrict__ dx) {
+    typedef GdwSmem<TT, NW> SM;
+    constexpr int NT = 64 * NW;
+    constexpr bool GATHER = NSRC_G > 0;
+    extern __shared__ __align__(16) unsigned char gdw_smem[];
+    unsigned char* s_a = gdw_smem;
+    float(*stage)[SM::STAGE_LD] =
+        reinterpret_cast<float(*)[SM::STAGE_LD]>(gdw_smem + SM::A_BYTES) + (threadIdx.x >> 6) * 32;
+    int* s_row = reinterpret_cast<int*>(gdw_smem + SM::A_BYTES + SM::STAGE_BYTES);   // [2][32*TT]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 31, h = lane >> 5;
+    const int t0 = blockIdx.x * 32 * TT;
+    const int rows_here = min(32 * TT, Tn - t0);
+    const int nks = (E + 15) / 16;
+    const __amdgpu_buffer_rsrc_t rs_dl = buf_rsrc(dlogits + (size_t)t0 * E, (size_t)rows_here * E * 4);
+    const __amdgpu_buffer_rsrc_t rs_w = buf_rsrc(Wg, (size_t)d * E * 4);
+    const __amdgpu_buffer_rsrc_t rs_dx = buf_rsrc(dx + (size_t)t0 * d, (size_t)rows_here * d * 2);
+    // 8 consecutive fp32 of a row (two 16-byte loads; E % 4 == 0: a quad is inside the row or beyond it)
+    auto load8_row = [&](__amdgpu_buffer_rsrc_t rs, int row_elems, int e0, float (&v)[8]) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const u32x4_buf_t q = __builtin_amdgcn_raw_buffer_load_b128(
+                rs, e0 + 4 * c < E ? (uint32_t)((row_elems + e0 + 4 * c) * 4) : BUF_OOB, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[4 * c + j] = __uint_as_float(q[j]);
+        }
+    };
+    // the workgroup's dlogits rows as MFMA operands: lane (r, h) of operand (tile, step) holds
+    // experts 16*step + 8h .. +7 of token 32*tile + r
+#pragma unroll
+    for (int i = 0; i < TT * GDW_KS * 64 / NT; ++i) {
+        const int it = threadIdx.x + i * NT;
+        const int l = it & 63, f = it >> 6;                 // f = tile*8 + step
+        const int ks = f & (GDW_KS - 1), tok = (f >> 3) * 32 + (l & 31);
+        float w8[8];
+        load8_row(rs_dl, tok * E, 16 * ks + 8 * (l >> 5), w8);   // rows beyond T read zeros
+        bf16x8_hw_t a_hi, a_lo;
+        split2_bf16(w8, a_hi, a_lo);
+        *reinterpret_cast<bf16x8_hw_t*>(s_a + (f * 2) * 1024 + l * 16) = a_hi;
+        *reinterpret_cast<bf16x8_hw_t*>(s_a + (f * 2 + 1) * 1024 + l * 16) = a_lo;
+    }
+    if constexpr (GATHER) {
+        for (int i = threadIdx.x; i < 2 * TT * 32; i += NT) {
+            const int j = i / (TT * 32), tl = i - j * (TT * 32), t = t0 + tl;
+            int row = -1;
+            if (t < Tn && j < k) {
+                const int sl = slot[(size_t)t * k + j];
+                if (sl >= 0) row = expert_idx[(size_t)t * k + j] * C + sl;
+            }
+            s_row[i] = row;
+        }
+    }
+    __syncthreads();
+
+    constexpr int LPR = GDX_COLS / 8;    // lanes per staged row (16-byte pieces of 8 bf16)
+    constexpr int RPI = 64 / LPR;        // rows per wave instruction
+    constexpr int NIT = 32 / RPI;        // row pieces per lane and tile
+    constexpr int NSRC = GATHER ? NSRC_G : 1;
+    const int er = lane / LPR, ec = (lane - er * LPR) * 8;
+    const int npass = (d + GDX_COLS - 1) / GDX_COLS;
+    for (int p = wave; p < npass; p += NW) {
+        const int i0 = p * GDX_COLS;
+        const int col = i0 + ec;
+        const bool col_ok = col < d;     // d % 8 == 0: a piece is inside the row or wholly beyond it
+        // What the product is added to (the token's kept rows of dxd, or dx itself), per tile.
+        u32x4_buf_t src[TT][NSRC][NIT];
+        uint32_t kept[TT];               // bit q*NIT + it: that piece counts (a dropped choice reads row 0 and is masked out)
+        auto request = [&](int tt) {
+            kept[tt] = 0;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int m = tt * 32 + er + it * RPI;
+                if constexpr (GATHER) {
+#pragma unroll
+                    for (int q = 0; q < NSRC; ++q) {
+                        const int row = s_row[q * TT * 32 + m];
+                        kept[tt] |= (row >= 0 ? 1u : 0u) << (q * NIT + it);
+                        src[tt][q][it] = *reinterpret_cast<const u32x4_buf_t*>(
+                            dxd + (size_t)max(row, 0) * d + (col_ok ? col : 0));
+                    }
+                } else {
+                    kept[tt] = ~0u;
+                    src[tt][0][it] = __builtin_amdgcn_raw_buffer_load_b128(
+                        rs_dx, col_ok ? (uint32_t)((m * d + col) * 2) : BUF_OOB, 0, 0);
+                }
+            }
+        };
+        request(0);                      // before the products of the pass: in flight under them
+        glm_f32x16 acc[TT][2];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[tt][c][v] = 0.0f;
+        // Gate rows are requested for two 16-expert steps at a time: the 128-byte line that holds
+        // experts 32j .. 32j+31 of a column is then touched by four back-to-back instructions and
+        // fetched from L2 once (a step apart, the other waves' lines have displaced it from L1).
+#pragma unroll
+        for (int kp = 0; kp < GDW_KS / 2; ++kp) {
+            if (2 * kp < nks) {                             // uniform
+                float w8[2][2][8];
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)             // rows beyond d fall outside rs_w, experts beyond E read zeros
+                        load8_row(rs_w, (i0 + 32 * c + r) * E, 16 * (2 * kp + u) + 8 * h, w8[u][c]);
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int ks = 2 * kp + u;
+                    bf16x8_hw_t b_hi[2], b_lo[2];
+#pragma unroll
+                    for (int c = 0; c < 2; ++c) split2_bf16(w8[u][c], b_hi[c], b_lo[c]);
+                    bf16x8_hw_t a_hi[TT], a_lo[TT];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        const unsigned char* pa = s_a + ((tt * GDW_KS + ks) * 2) * 1024 + lane * 16;
+                        a_hi[tt] = *reinterpret_cast<const bf16x8_hw_t*>(pa);
+                        a_lo[tt] = *reinterpret_cast<const bf16x8_hw_t*>(pa + 1024);
+                    }
+                    // the three partial products of a tile are far apart: no MFMA waits for its predecessor
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int c = 0; c < 2; ++c)
+                            acc[tt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo[tt], b_hi[c], acc[tt][c], 0, 0, 0);
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int c = 0; c < 2; ++c)
+                            acc[tt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[tt], b_lo[c], acc[tt][c], 0, 0, 0);
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int c = 0; c < 2; ++c)
+                            acc[tt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi[tt], b_hi[c], acc[tt][c], 0, 0, 0);
+                }
+            }
+        }
+        // the other tiles' sources as registers come free, each well before its use
+        request(1);
+        if constexpr (TT > 2) request(2);
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            if (tt >= 1 && tt + 2 < TT) request(tt + 2);
+            // accumulator element v of lane l: column l%32, token row 8*(v/4) + 4*(l/32) + v%4
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) stage[8 * (v >> 2) + 4 * h + (v & 3)][32 * c + r] = acc[tt][c][v];
+            // LDS operations of a wave execute in order: the row pieces read below are complete
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const int ml = er + it * RPI;
+                float inc[8];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const float4 w4 = *reinterpret_cast<const float4*>(&stage[ml][ec + 4 * q]);
+                    inc[4 * q] = w4.x; inc[4 * q + 1] = w4.y; inc[4 * q + 2] = w4.z; inc[4 * q + 3] = w4.w;
+                }
+#pragma unroll
+                for (int q = 0; q < NSRC; ++q) {
+                    const bool on = (kept[tt] >> (q * NIT + it)) & 1u;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        inc[2 * j] += on ? __uint_as_float(src[tt][q][it][j] << 16) : 0.0f;
+                        inc[2 * j + 1] += on ? __uint_as_float(src[tt][q][it][j] & 0xffff0000u) : 0.0f;
+                    }
+                }
+                // stores beyond T or d are dropped by the range check
+                BufChunk<bf16_t>::store(rs_dx, col_ok ? (uint32_t)(((tt * 32 + ml) * d + col) * 2) : BUF_OOB, inc);
+            }
+        }
+    }
+}
+
+#ifndef GDW_TT
+#define GDW_TT 4
+#define GDW_NW 8
+#endif
 template <typename T>
 static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const float* Wg,
                                    const float* dlogits, float* dWg, void* dx, const void* dxd,
@@ -935,7 +1141,33 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
                                                                                (const T*)x, dlogits, partial, eps, seed);
     const int n = s->d_model * s->E;
     gate_dwg_reduce_kernel<<<ceil_div(n, 256), 256, 0, st>>>(n, nch_used, partial, dWg);
-    if (dx) {
+    if (dx && sizeof(T) == 2 && eps == 0.0f && s->E > 32 && s->E <= 16 * GDW_KS && s->E % 4 == 0 &&
+        ceil_div(s->T, 32 * GDW_TT) >= 192) {
+        // once the larger token tiles still give every compute unit a workgroup or two
+        typedef GdwSmem<GDW_TT, GDW_NW> SM;
+        static unsigned long long opted = 0;     // bit per device: opt in to more than 64 KB of LDS
+        int dev = 0;
+        (void)hipGetDevice(&dev);
+        bool ok = true;
+        if (dev < 64 && !(opted >> dev & 1)) {
+            ok = true;
+            const void* kerns[3] = {(const void*)gate_dx_wide_kernel<0, GDW_TT, GDW_NW>,
+                                    (const void*)gate_dx_wide_kernel<1, GDW_TT, GDW_NW>,
+                                    (const void*)gate_dx_wide_kernel<2, GDW_TT, GDW_NW>};
+            for (const void* kn : kerns)
+                ok = ok && hipFuncSetAttribute(kn, hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES) == hipSuccess;
+            if (ok) opted |= 1ull << dev;
+        }
+        if (ok) {   // else: the error is left for launch_status()
+            const int grid_w = ceil_div(s->T, 32 * GDW_TT);
+#define GDWL(NS, DXD, EI, SL) gate_dx_wide_kernel<NS, GDW_TT, GDW_NW><<<grid_w, 64 * GDW_NW, SM::BYTES, st>>>( \
+    s->T, s->d_model, s->E, s->k, s->capacity, dlogits, Wg, DXD, EI, SL, (bf16_t*)dx)
+            if (!dxd) GDWL(0, nullptr, nullptr, nullptr);
+            else if (s->k == 1) GDWL(1, (const bf16_t*)dxd, expert_idx, slot);
+            else GDWL(2, (const bf16_t*)dxd, expert_idx, slot);
+#undef GDWL
+        }
+    } else if (dx) {
         const int grid_dx = ceil_div(s->T, 32);
 #define GDX(EB, VEC, GA) gate_dx_kernel<T, EB, VEC, GA><<<grid_dx, 64 * GDX_WAVES, 0, st>>>( \
     s->T, s->d_model, s->E, s->k, s->capacity, dlogits, Wg, (const T*)dxd, expert_idx, slot, (T*)dx, eps, seed)

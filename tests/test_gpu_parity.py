@@ -225,6 +225,11 @@ def test_argument_errors_leave_outputs_untouched():
     (2049, 320, 40, 1, 300, I.BF16, 0.0),     # two 32-expert blocks
     (640, 128, 8, 2, 96, I.BF16, 0.05),       # with gate jitter
     (4096, 1024, 32, 2, 512, I.BF16, 0.0),    # cfg3's row length
+    # many experts and enough tokens for the 128-token workgroups: ragged T, d no multiple of 64,
+    # expert counts that leave the last 16-expert step partly or wholly empty
+    (24577, 136, 128, 2, 500, I.BF16, 0.0),
+    (25000, 200, 100, 1, 300, I.BF16, 0.0),
+    (24600, 72, 36, 2, 900, I.BF16, 0.0),
 ])
 def test_dispatch_backward_fused_with_gate_projection_backward(T, d, E, k, C, dtype, eps):
     """dx = (sum of the token's kept rows of dxd) + dlogits Wg^T in one call, on a
@@ -267,9 +272,34 @@ def test_dispatch_backward_fused_with_gate_projection_backward(T, d, E, k, C, dt
     dx_ref = O.combine_fwd(dxd, expert_idx, slot) + dx_gate * noise
     assert G.rel_l2(G.host(dWg), dWg_ref) <= 1e-5
     assert G.rel_l2(G.host(dx), dx_ref) <= G.TOL[dtype]
+    G.assert_rows("dx", G.host(dx), dx_ref, G.TOL[dtype])
     none_kept = (slot < 0).all(axis=1)
     assert none_kept.any()
     assert G.rel_l2(G.host(dx)[none_kept], (dx_gate * noise)[none_kept]) <= G.TOL[dtype]
+
+
+def test_gate_projection_backward_accumulates_with_many_experts():
+    """dx += dlogits Wg^T (no gather) on the 128-token workgroups: ragged T, 64 experts, a preset dx."""
+    T, d, E = 24700, 104, 64
+    rng = np.random.default_rng(9)
+    x = I.round_to_bf16(rng.standard_normal((T, d)).astype(np.float32))
+    dx0 = I.round_to_bf16(rng.standard_normal((T, d)).astype(np.float32))
+    Wg = (rng.standard_normal((d, E)) * 0.5).astype(np.float32)
+    dl = (rng.standard_normal((T, E)) * 0.5).astype(np.float32)
+    shape = B.make_shape(T, d, 8, E, 1, 4, I.BF16, I.GELU)
+    ws = torch.empty(B.moe_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    dWg = torch.empty((d, E), dtype=torch.float32, device="cuda")
+    dx = torch.full((T + 2, d), 3.0, dtype=torch.bfloat16, device="cuda")
+    dx[1:T + 1] = G.to_dev(dx0, I.BF16)
+    print("[gpu] gate projection backward, accumulate form, 64 experts", flush=True)
+    B.moe_gate_logits_bwd(shape, G.to_dev(x, I.BF16), G.to_dev(Wg, I.F32), G.to_dev(dl, I.F32), dWg, dx[1:T + 1], ws)
+    torch.cuda.synchronize()
+    dWg_ref, dx_ref = O.gate_logits_bwd(x, Wg, dl)
+    got = G.host(dx)
+    assert (got[0] == 3.0).all() and (got[T + 1] == 3.0).all()
+    assert G.rel_l2(G.host(dWg), dWg_ref) <= 1e-5
+    assert G.rel_l2(got[1:T + 1], dx0 + dx_ref) <= G.TOL[I.BF16]
+    G.assert_rows("dx", got[1:T + 1], dx0 + dx_ref, G.TOL[I.BF16])
 
 
 def test_mfma_rate_aid_counts_what_it_claims():
