@@ -156,13 +156,14 @@ __global__ __launch_bounds__(TopkGeom<LPT>::THREADS) void gate_topk_kernel(
             const float sum = part;
             if (valid) {
                 float* pr = probs + (size_t)t * E;
+                const float inv = 1.0f / sum;      // one division per lane; the products are within an ulp of ex / sum
                 if (vec) {
                     if (e4 < E)
-                        *reinterpret_cast<float4*>(pr + e4) = make_float4(ex[0] / sum, ex[1] / sum, ex[2] / sum, ex[3] / sum);
+                        *reinterpret_cast<float4*>(pr + e4) = make_float4(ex[0] * inv, ex[1] * inv, ex[2] * inv, ex[3] * inv);
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        if (e4 + i < E) pr[e4 + i] = ex[i] / sum;
+                        if (e4 + i < E) pr[e4 + i] = ex[i] * inv;
                 }
                 if (gl == 0) {
                     const float p0 = 1.0f / sum;   // = exp(0) / sum
