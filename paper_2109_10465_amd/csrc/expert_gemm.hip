@@ -828,21 +828,6 @@ static int num_cus() {
     return n;
 }
 
-// A kernel that uses more than 64 KB of the CU's 160 KB LDS has to opt in, once per kernel
-// instance and device (`done` is that instance's bit mask over device ids).
-static bool lds_opt_in(const void* kern, size_t smem, unsigned long long* done) {
-    if (smem <= 64 * 1024) return true;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
-    if (__atomic_load_n(done, __ATOMIC_ACQUIRE) >> dev & 1ull) return true;
-    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) {
-        (void)hipGetLastError();
-        return false;
-    }
-    __atomic_fetch_or(done, 1ull << dev, __ATOMIC_RELEASE);
-    return true;
-}
-
 #ifndef MOE_GEMM_NWN
 #define MOE_GEMM_NWN 4
 #endif

@@ -369,31 +369,25 @@ __global__ __launch_bounds__(GLL_THREADS, 1) void gate_logits_lds_kernel(
 }
 
 template <int TT>
-static void launch_gate_logits_lds(const moe_shape* s, const void* x, const float* Wg, const float* bias,
+static bool launch_gate_logits_lds(const moe_shape* s, const void* x, const float* Wg, const float* bias,
                                    float* logits, hipStream_t st) {
-    static unsigned long long opted = 0;     // bit per device: opt in to more than 64 KB of LDS
-    int dev = 0;
-    (void)hipGetDevice(&dev);
-    if (dev < 64 && !(opted >> dev & 1)) {
-        if (hipFuncSetAttribute((const void*)gate_logits_lds_kernel<TT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                GllSmem<TT>::BYTES) != hipSuccess) return;   // the launch below then fails and is reported
-        opted |= 1ull << dev;
-    }
+    static unsigned long long opted = 0;
+    if (!lds_opt_in((const void*)gate_logits_lds_kernel<TT>, GllSmem<TT>::BYTES, &opted)) return false;
     gate_logits_lds_kernel<TT><<<ceil_div(s->T, 32 * TT), GLL_THREADS, GllSmem<TT>::BYTES, st>>>(
         s->T, s->d_model, s->E, (const bf16_t*)x, Wg, bias, logits);
+    return true;
 }
 
 template <typename T>
-static void launch_gate_logits(const moe_shape* s, const void* x, const float* Wg, const float* bias,
+static bool launch_gate_logits(const moe_shape* s, const void* x, const float* Wg, const float* bias,
                                float* logits, float eps, uint64_t seed, hipStream_t st) {
     if constexpr (sizeof(T) == 2) {
         // bias rows are read as 16 bytes: the pointer must be 16-byte aligned like every tensor here
         if (eps == 0.0f && s->E > 32 && s->E <= 128 && s->E % 4 == 0 && ((uintptr_t)logits & 15) == 0 &&
             ((uintptr_t)bias & 15) == 0 && ((uintptr_t)Wg & 15) == 0) {
             // 128 tokens per workgroup when that still gives most compute units a workgroup
-            if (ceil_div(s->T, 128) >= 192) launch_gate_logits_lds<4>(s, x, Wg, bias, logits, st);
-            else launch_gate_logits_lds<2>(s, x, Wg, bias, logits, st);
-            return;
+            if (ceil_div(s->T, 128) >= 192) return launch_gate_logits_lds<4>(s, x, Wg, bias, logits, st);
+            return launch_gate_logits_lds<2>(s, x, Wg, bias, logits, st);
         }
     }
     // two token tiles per workgroup on the bf16 matrix path with more than 32 experts
@@ -412,6 +406,7 @@ static void launch_gate_logits(const moe_shape* s, const void* x, const float* W
         else if (s->E <= 128) GLM(4, false, TT2); else GLM(8, false, 1);
     }
 #undef GLM
+    return true;
 }
 
 static int gate_logits_impl(const moe_shape* shape, const void* x, const float* Wg,
@@ -420,9 +415,10 @@ static int gate_logits_impl(const moe_shape* shape, const void* x, const float* 
     if (rc) return rc;
     if (!x || !Wg || !logits) return MOE_ERR_NULL;
     if (!(eps >= 0.0f && eps < 1.0f)) return MOE_ERR_SHAPE;
-    if (shape->dtype == MOE_BF16) launch_gate_logits<bf16_t>(shape, x, Wg, bias_or_null, logits, eps, seed, (hipStream_t)stream);
-    else launch_gate_logits<float>(shape, x, Wg, bias_or_null, logits, eps, seed, (hipStream_t)stream);
-    return launch_status();
+    const bool ok = shape->dtype == MOE_BF16
+        ? launch_gate_logits<bf16_t>(shape, x, Wg, bias_or_null, logits, eps, seed, (hipStream_t)stream)
+        : launch_gate_logits<float>(shape, x, Wg, bias_or_null, logits, eps, seed, (hipStream_t)stream);
+    return ok ? launch_status() : MOE_ERR_LAUNCH;
 }
 
 extern "C" int moe_gate_logits(const moe_shape* shape, const void* x, const float* Wg,
@@ -1120,7 +1116,7 @@ __global__ __launch_bounds__(64 * NW, TT == 2 ? 2 : 1) void gate_dx_wide_kernel(
 #define GDW_NW 8
 #endif
 template <typename T>
-static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const float* Wg,
+static bool launch_gate_logits_bwd(const moe_shape* s, const void* x, const float* Wg,
                                    const float* dlogits, float* dWg, void* dx, const void* dxd,
                                    const int32_t* expert_idx, const int32_t* slot, float* partial, float eps,
                                    uint64_t seed, hipStream_t st) {
@@ -1128,45 +1124,32 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
     const int nch_used = ceil_div(s->T, tpc);
     dim3 grid(ceil_div(s->d_model, GW_COLS), nch_used, ceil_div(s->E, 32));
     constexpr size_t red_bytes = (size_t)GW_WAVES * GW_COLS * 32 * sizeof(float);   // 128 KB: opt in beyond 64 KB
-    static const hipError_t attr0 = hipFuncSetAttribute(
-        (const void*)gate_dwg_partial_kernel<T, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)red_bytes);
-    static const hipError_t attr1 = hipFuncSetAttribute(
-        (const void*)gate_dwg_partial_kernel<T, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)red_bytes);
-    (void)attr0; (void)attr1;
-    if (eps != 0.0f)
+    static unsigned long long opted_w[2] = {0, 0};
+    if (eps != 0.0f) {
+        if (!lds_opt_in((const void*)gate_dwg_partial_kernel<T, true>, red_bytes, &opted_w[1])) return false;
         gate_dwg_partial_kernel<T, true><<<grid, 64 * GW_WAVES, red_bytes, st>>>(s->T, s->d_model, s->E, tpc,
                                                                               (const T*)x, dlogits, partial, eps, seed);
-    else
+    } else {
+        if (!lds_opt_in((const void*)gate_dwg_partial_kernel<T, false>, red_bytes, &opted_w[0])) return false;
         gate_dwg_partial_kernel<T, false><<<grid, 64 * GW_WAVES, red_bytes, st>>>(s->T, s->d_model, s->E, tpc,
                                                                                (const T*)x, dlogits, partial, eps, seed);
+    }
     const int n = s->d_model * s->E;
     gate_dwg_reduce_kernel<<<ceil_div(n, 256), 256, 0, st>>>(n, nch_used, partial, dWg);
     if (dx && sizeof(T) == 2 && eps == 0.0f && s->E > 32 && s->E <= 16 * GDW_KS && s->E % 4 == 0 &&
         ceil_div(s->T, 32 * GDW_TT) >= 192) {
-        // once the larger token tiles still give every compute unit a workgroup or two
+        // 128 tokens per workgroup once that still gives most compute units a workgroup
         typedef GdwSmem<GDW_TT, GDW_NW> SM;
-        static unsigned long long opted = 0;     // bit per device: opt in to more than 64 KB of LDS
-        int dev = 0;
-        (void)hipGetDevice(&dev);
-        bool ok = true;
-        if (dev < 64 && !(opted >> dev & 1)) {
-            ok = true;
-            const void* kerns[3] = {(const void*)gate_dx_wide_kernel<0, GDW_TT, GDW_NW>,
-                                    (const void*)gate_dx_wide_kernel<1, GDW_TT, GDW_NW>,
-                                    (const void*)gate_dx_wide_kernel<2, GDW_TT, GDW_NW>};
-            for (const void* kn : kerns)
-                ok = ok && hipFuncSetAttribute(kn, hipFuncAttributeMaxDynamicSharedMemorySize, SM::BYTES) == hipSuccess;
-            if (ok) opted |= 1ull << dev;
-        }
-        if (ok) {   // else: the error is left for launch_status()
-            const int grid_w = ceil_div(s->T, 32 * GDW_TT);
-#define GDWL(NS, DXD, EI, SL) gate_dx_wide_kernel<NS, GDW_TT, GDW_NW><<<grid_w, 64 * GDW_NW, SM::BYTES, st>>>( \
-    s->T, s->d_model, s->E, s->k, s->capacity, dlogits, Wg, DXD, EI, SL, (bf16_t*)dx)
-            if (!dxd) GDWL(0, nullptr, nullptr, nullptr);
-            else if (s->k == 1) GDWL(1, (const bf16_t*)dxd, expert_idx, slot);
-            else GDWL(2, (const bf16_t*)dxd, expert_idx, slot);
+        static unsigned long long opted_x[3] = {0, 0, 0};
+        const int grid_w = ceil_div(s->T, 32 * GDW_TT);
+#define GDWL(NS, DXD, EI, SL) do { \
+    if (!lds_opt_in((const void*)gate_dx_wide_kernel<NS, GDW_TT, GDW_NW>, SM::BYTES, &opted_x[NS])) return false; \
+    gate_dx_wide_kernel<NS, GDW_TT, GDW_NW><<<grid_w, 64 * GDW_NW, SM::BYTES, st>>>( \
+        s->T, s->d_model, s->E, s->k, s->capacity, dlogits, Wg, DXD, EI, SL, (bf16_t*)dx); } while (0)
+        if (!dxd) GDWL(0, nullptr, nullptr, nullptr);
+        else if (s->k == 1) GDWL(1, (const bf16_t*)dxd, expert_idx, slot);
+        else GDWL(2, (const bf16_t*)dxd, expert_idx, slot);
 #undef GDWL
-        }
     } else if (dx) {
         const int grid_dx = ceil_div(s->T, 32);
 #define GDX(EB, VEC, GA) gate_dx_kernel<T, EB, VEC, GA><<<grid_dx, 64 * GDX_WAVES, 0, st>>>( \
@@ -1178,6 +1161,7 @@ static void launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
 #undef GDXE
 #undef GDX
     }
+    return true;
 }
 
 static int gate_logits_bwd_impl(const moe_shape* shape, const void* x, const float* Wg, const float* dlogits,
@@ -1189,11 +1173,10 @@ static int gate_logits_bwd_impl(const moe_shape* shape, const void* x, const flo
     if (!x || !Wg || !dlogits || !dWg) return MOE_ERR_NULL;
     if (!(eps >= 0.0f && eps < 1.0f)) return MOE_ERR_SHAPE;
     if (!ws || ((uintptr_t)ws & 255) || ws_bytes < gate_logits_bwd_ws_bytes(shape)) return MOE_ERR_WORKSPACE;
-    if (shape->dtype == MOE_BF16)
-        launch_gate_logits_bwd<bf16_t>(shape, x, Wg, dlogits, dWg, dx_accum, dxd, expert_idx, slot, (float*)ws, eps, seed, (hipStream_t)stream);
-    else
-        launch_gate_logits_bwd<float>(shape, x, Wg, dlogits, dWg, dx_accum, dxd, expert_idx, slot, (float*)ws, eps, seed, (hipStream_t)stream);
-    return launch_status();
+    const bool ok = shape->dtype == MOE_BF16
+        ? launch_gate_logits_bwd<bf16_t>(shape, x, Wg, dlogits, dWg, dx_accum, dxd, expert_idx, slot, (float*)ws, eps, seed, (hipStream_t)stream)
+        : launch_gate_logits_bwd<float>(shape, x, Wg, dlogits, dWg, dx_accum, dxd, expert_idx, slot, (float*)ws, eps, seed, (hipStream_t)stream);
+    return ok ? launch_status() : MOE_ERR_LAUNCH;
 }
 
 extern "C" int moe_gate_logits_bwd(const moe_shape* shape, const void* x, const float* Wg,

@@ -295,6 +295,21 @@ static inline int check_shape(const moe_shape* s) {
     if ((int64_t)s->T * s->k >= (1 << 30) || (int64_t)s->E * s->capacity >= (1 << 30)) return MOE_ERR_SHAPE;
     return MOE_OK;
 }
+// A kernel that uses more than 64 KB of the CU's 160 KB LDS has to opt in, once per kernel
+// instance and device (`done` is that instance's bit mask over device ids).
+static inline bool lds_opt_in(const void* kern, size_t smem, unsigned long long* done) {
+    if (smem <= 64 * 1024) return true;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    if (__atomic_load_n(done, __ATOMIC_ACQUIRE) >> dev & 1ull) return true;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    __atomic_fetch_or(done, 1ull << dev, __ATOMIC_RELEASE);
+    return true;
+}
+
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_LAUNCH; }
 
 // Workspace layouts (bytes), shared by moe_workspace_bytes and the entry points.

@@ -21,14 +21,14 @@
 // case; balanced routing makes step 3 a few microseconds.
 #include "moe_common.h"
 
-#define CHUNK 256       // tokens per histogram chunk (= per gate_topk / route_place workgroup)
+#define CHUNK 256       // tokens per histogram chunk (= per route_place workgroup; gate_topk: see topk_sub)
 #define RANK_TILE 256   // candidates per route_rank workgroup
 #define RANK_PARTS 4    // threads per candidate: each counts over a quarter of every staged tile
 #define RANK_PAIR_TILES 4   // segments longer than this many tiles are ranked through key buckets
 #define RANK_BUCKETS 1024   // = threads of a route_rank workgroup
 
 struct RouteWs {
-    int32_t* hist;        // [nchunk][k*E] candidates per chunk and segment
+    int32_t* hist;        // [nchunk * topk_sub(E)][k*E] candidates per chunk part and segment
     int32_t* seg_start;   // [G][k*E+1] segment seg = e*k+j of group g starts here in seg_tok/seg_key
     int32_t* tile_start;  // [G][k*E+1] prefix, inside group g, of ceil(n_seg / RANK_TILE)
     int32_t* goff;        // [G][E] rows kept for expert e in the groups before g
@@ -37,11 +37,15 @@ struct RouteWs {
 };
 
 static inline int n_chunks(const moe_shape* s) { return ceil_div(s->T, CHUNK); }
+// With more than 64 experts a chunk's tokens are shared by 2 (4 beyond 128 experts) gate_topk
+// workgroups, each with its own histogram row: a workgroup of 1024 threads then still takes 4
+// rounds per chunk part, and a batch of 32 k tokens gives 256 workgroups instead of 128.
+static inline int topk_sub(int E) { return E > 128 ? 4 : (E > 64 ? 2 : 1); }
 
 // Sized for the largest possible number of groups (one per chunk).
 size_t route_ws_bytes(const moe_shape* s) {
     const size_t kE = (size_t)s->k * s->E, Tk = (size_t)s->T * s->k, G = (size_t)n_chunks(s);
-    return align_up(G * kE * 4, 256) + 2 * align_up(G * (kE + 1) * 4, 256) + align_up(G * s->E * 4, 256) +
+    return align_up(G * topk_sub(s->E) * kE * 4, 256) + 2 * align_up(G * (kE + 1) * 4, 256) + align_up(G * s->E * 4, 256) +
            2 * align_up(Tk * 4, 256);
 }
 
@@ -49,7 +53,7 @@ static RouteWs carve(const moe_shape* s, void* ws) {
     const size_t kE = (size_t)s->k * s->E, Tk = (size_t)s->T * s->k, G = (size_t)n_chunks(s);
     char* p = (char*)ws;
     RouteWs r;
-    r.hist = (int32_t*)p;       p += align_up(G * kE * 4, 256);
+    r.hist = (int32_t*)p;       p += align_up(G * topk_sub(s->E) * kE * 4, 256);
     r.seg_start = (int32_t*)p;  p += align_up(G * (kE + 1) * 4, 256);
     r.tile_start = (int32_t*)p; p += align_up(G * (kE + 1) * 4, 256);
     r.goff = (int32_t*)p;       p += align_up(G * s->E * 4, 256);
@@ -74,9 +78,11 @@ __device__ __forceinline__ bool better(float va, int ia, float vb, int ib) {
 // one memory latency, not one per round.
 template <int LPT>
 struct TopkGeom {
-    static constexpr int ROUNDS = CHUNK * LPT <= 1024 ? 1 : CHUNK * LPT / 1024;
-    static constexpr int THREADS = CHUNK * LPT / ROUNDS;
-    static constexpr int TPI = CHUNK / ROUNDS;                  // tokens per round
+    static constexpr int SUB = LPT >= 32 ? LPT / 16 : 1;        // workgroups per chunk (= topk_sub(E))
+    static constexpr int TOK = CHUNK / SUB;                     // tokens per workgroup
+    static constexpr int ROUNDS = TOK * LPT <= 1024 ? 1 : TOK * LPT / 1024;
+    static constexpr int THREADS = TOK * LPT / ROUNDS;
+    static constexpr int TPI = TOK / ROUNDS;                    // tokens per round
     static constexpr int BATCH = ROUNDS < 8 ? ROUNDS : 8;       // rounds whose logits are in flight together
 };
 
@@ -96,7 +102,7 @@ __global__ __launch_bounds__(TopkGeom<LPT>::THREADS) void gate_topk_kernel(
         float lq[G::BATCH][4];
 #pragma unroll
         for (int u = 0; u < G::BATCH; ++u) {
-            const int t = blockIdx.x * CHUNK + (it0 + u) * G::TPI + slot;
+            const int t = blockIdx.x * G::TOK + (it0 + u) * G::TPI + slot;
 #pragma unroll
             for (int i = 0; i < 4; ++i) lq[u][i] = -INFINITY;
             if (t < T) {
@@ -115,7 +121,7 @@ __global__ __launch_bounds__(TopkGeom<LPT>::THREADS) void gate_topk_kernel(
         }
 #pragma unroll
         for (int u = 0; u < G::BATCH; ++u) {
-            const int t = blockIdx.x * CHUNK + (it0 + u) * G::TPI + slot;
+            const int t = blockIdx.x * G::TOK + (it0 + u) * G::TPI + slot;
             const bool valid = t < T;   // uniform within a token's lane group
             const float(&l)[4] = lq[u];
             // the lane's own best two (ascending ids, strict comparisons).  A NaN logit never
@@ -205,7 +211,7 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
 // g, which routes on its own with Cg slots per expert; its candidates occupy
 // positions [g*cpg*CHUNK*k, ...) of seg_tok/seg_key.  One group = plain routing.
 __global__ __launch_bounds__(CHUNK) void route_place_kernel(
-    int T, int E, int k, int Cg, int nchunk, int cpg, const int32_t* __restrict__ expert_idx,
+    int T, int E, int k, int Cg, int nchunk, int cpg, int sub, const int32_t* __restrict__ expert_idx,
     const float* __restrict__ keys, const int32_t* __restrict__ hist,
     int32_t* __restrict__ seg_start, int32_t* __restrict__ tile_start, int32_t* __restrict__ goff,
     int32_t* __restrict__ expert_count, int32_t* __restrict__ expert_demand,
@@ -232,19 +238,20 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
     }
     __syncthreads();
     {
-        // the group's histograms are one array [chunk][segment]: every thread sums a
-        // strided share of it (8 loads in flight) and adds its part with integer LDS
+        // the group's histograms are one array [chunk part][segment]: every thread sums a
+        // strided share of it (16 loads in flight) and adds its part with integer LDS
         // atomics; entries of chunks before this one also count towards the prefix
-        const int32_t* gh = hist + (size_t)c_lo * kE;
-        const int n = (c_hi - c_lo) * kE, before = (chunk - c_lo) * kE;
+        const int32_t* gh = hist + (size_t)c_lo * sub * kE;      // sub histogram rows per chunk
+        const int n = (c_hi - c_lo) * sub * kE, before = (chunk - c_lo) * sub * kE;
         const bool fixed_seg = CHUNK % kE == 0;   // then a thread always meets the same segment
+        constexpr int HU = 16;
         int tot = 0, pre = 0;
-        for (int i0 = threadIdx.x; i0 < n; i0 += 8 * CHUNK) {
-            int v[8];
+        for (int i0 = threadIdx.x; i0 < n; i0 += HU * CHUNK) {
+            int v[HU];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = i0 + u * CHUNK < n ? gh[i0 + u * CHUNK] : 0;
+            for (int u = 0; u < HU; ++u) v[u] = i0 + u * CHUNK < n ? gh[i0 + u * CHUNK] : 0;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < HU; ++u) {
                 const int idx = i0 + u * CHUNK;
                 if (fixed_seg) {
                     tot += v[u];
@@ -275,8 +282,8 @@ __global__ __launch_bounds__(CHUNK) void route_place_kernel(
         }
         for (int gg = 0; gg < (ngroups == 1 ? 0 : upto); ++gg) {
             int dem = 0;
-            const int hi = min((gg + 1) * cpg, nchunk);
-            int c = gg * cpg;
+            const int hi = min((gg + 1) * cpg, nchunk) * sub;   // histogram rows of group gg
+            int c = gg * cpg * sub;
             for (; c + 8 <= hi; c += 8) {
                 int v[8];
 #pragma unroll
@@ -539,11 +546,11 @@ static int route_impl(const moe_shape* shape, int G, const float* logits, const 
     const int nchunk = n_chunks(shape);
     const int cpg = G == 1 ? nchunk : T / G / CHUNK;    // chunks per group
     const int Cg = C / G;
-#define GATE(LPT) gate_topk_kernel<LPT><<<nchunk, TopkGeom<LPT>::THREADS, 0, st>>>(T, E, k, logits, probs, expert_idx, gate_w, r.hist)
+#define GATE(LPT) gate_topk_kernel<LPT><<<nchunk * TopkGeom<LPT>::SUB, TopkGeom<LPT>::THREADS, 0, st>>>(T, E, k, logits, probs, expert_idx, gate_w, r.hist)
     if (E <= 4) GATE(1); else if (E <= 8) GATE(2); else if (E <= 16) GATE(4); else if (E <= 32) GATE(8);
     else if (E <= 64) GATE(16); else if (E <= 128) GATE(32); else GATE(64);
 #undef GATE
-    route_place_kernel<<<nchunk, CHUNK, 0, st>>>(T, E, k, Cg, nchunk, cpg, expert_idx, rts_keys_or_null, r.hist,
+    route_place_kernel<<<nchunk, CHUNK, 0, st>>>(T, E, k, Cg, nchunk, cpg, topk_sub(E), expert_idx, rts_keys_or_null, r.hist,
                                                  r.seg_start, r.tile_start, r.goff, expert_count,
                                                  expert_demand, r.seg_tok, r.seg_key);
     const int Tg = G == 1 ? T : T / G;
