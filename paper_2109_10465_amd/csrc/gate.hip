@@ -525,11 +525,14 @@ size_t gate_logits_bwd_ws_bytes(const moe_shape* s) {
     return align_up((size_t)ceil_div(s->T, gw_chunk_tokens(s)) * s->d_model * s->E * 4, 256);
 }
 
+#ifndef GW_MINB
+#define GW_MINB 2
+#endif
 template <typename T, bool JIT>
-__global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
+__global__ __launch_bounds__(64 * GW_WAVES, JIT ? 1 : GW_MINB) void gate_dwg_partial_kernel(
     int Tn, int d, int E, int tok_per_chunk, const T* __restrict__ x,
     const float* __restrict__ dlogits, float* __restrict__ partial, float jitter_eps, uint64_t seed) {
-    extern __shared__ __align__(16) float gw_red[];      // [wave][256 columns][32 experts]
+    extern __shared__ __align__(16) float gw_red[];      // [2][256 columns][32 experts]
     constexpr int GRP = 4;                               // token pairs whose loads are in flight together (x2 buffers)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, h = lane >> 5;
@@ -624,21 +627,38 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
     }
     }
     // accumulator v of tile c, lane l: column i0 + 8*(8*(v/4) + 4*(l/32) + v%4) + c, expert e0 + l%32
+    // The four waves' tiles are added as (w0 + w2) + (w1 + w3) through two staged tiles (64 KB, so
+    // that two workgroups share a compute unit): waves 2, 3 stage theirs, waves 0, 1 add their own
+    // in place, every thread then adds the two sums.  A fixed order: reproducible.
+    static_assert(GW_WAVES == 4, "the reduction below pairs wave w with wave w + 2");
+    if (wave >= 2) {
 #pragma unroll
-    for (int c = 0; c < 8; ++c)
+        for (int c = 0; c < 8; ++c)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int m = 8 * (v >> 2) + 4 * h + (v & 3);
-            gw_red[(wave * GW_COLS + 8 * m + c) * 32 + r] = acc[c][v];
+            for (int v = 0; v < 16; ++v)
+                gw_red[((wave - 2) * GW_COLS + 8 * (8 * (v >> 2) + 4 * h + (v & 3)) + c) * 32 + r] = acc[c][v];
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float* p = &gw_red[(wave * GW_COLS + 8 * (8 * (v >> 2) + 4 * h + (v & 3)) + c) * 32 + r];
+                *p = acc[c][v] + *p;
+            }
+            __builtin_amdgcn_sched_barrier(0);           // one tile's 16 reads at a time
         }
+    }
     __syncthreads();
     // 4 experts per thread and pass; every LDS read of the loop is issued before the first add
     constexpr int NPASS = GW_COLS * 32 / 4 / (64 * GW_WAVES);
-    float4 part[NPASS][GW_WAVES];
+    constexpr int NSUM = 2;
+    float4 part[NPASS][NSUM];
 #pragma unroll
     for (int q = 0; q < NPASS; ++q)
 #pragma unroll
-        for (int w = 0; w < GW_WAVES; ++w)
+        for (int w = 0; w < NSUM; ++w)
             part[q][w] = *reinterpret_cast<const float4*>(
                 &gw_red[(size_t)(w * GW_COLS) * 32 + (size_t)(q * 64 * GW_WAVES + threadIdx.x) * 4]);
     const bool e_vec = (E & 3) == 0;
@@ -648,7 +668,7 @@ __global__ __launch_bounds__(64 * GW_WAVES) void gate_dwg_partial_kernel(
         const int il = o >> 5, e = o & 31;
         float4 sum = part[q][0];
 #pragma unroll
-        for (int w = 1; w < GW_WAVES; ++w) {   // in wave order: reproducible
+        for (int w = 1; w < NSUM; ++w) {
             sum.x += part[q][w].x; sum.y += part[q][w].y; sum.z += part[q][w].z; sum.w += part[q][w].w;
         }
         if (i0 + il < d) {
@@ -1123,7 +1143,7 @@ static bool launch_gate_logits_bwd(const moe_shape* s, const void* x, const floa
     const int tpc = gw_chunk_tokens(s);
     const int nch_used = ceil_div(s->T, tpc);
     dim3 grid(ceil_div(s->d_model, GW_COLS), nch_used, ceil_div(s->E, 32));
-    constexpr size_t red_bytes = (size_t)GW_WAVES * GW_COLS * 32 * sizeof(float);   // 128 KB: opt in beyond 64 KB
+    constexpr size_t red_bytes = (size_t)2 * GW_COLS * 32 * sizeof(float);   // two staged tiles: 64 KB
     static unsigned long long opted_w[2] = {0, 0};
     if (eps != 0.0f) {
         if (!lds_opt_in((const void*)gate_dwg_partial_kernel<T, true>, red_bytes, &opted_w[1])) return false;
