@@ -156,13 +156,13 @@ int moe_gate_route_grouped(const moe_shape* shape, int32_t n_groups, const float
  * scratch memory is a device array built into the library instead of a caller
  * workspace, so the call allocates and frees nothing.  Limits and rules:
  *  - the shape's routing scratch must fit moe_gate_route_static_max_bytes()
- *    (4 MiB; enough for T = 65536, k = 2 with any E <= 256), else
+ *    (5 MiB; enough for T = 65536, k = 2 with any E <= 256), else
  *    MOE_ERR_WORKSPACE is returned before anything is enqueued;
  *  - every GPU has one such array and every call on that GPU uses it: calls that
  *    may overlap on one GPU (two streams, two threads) race and must be ordered
  *    by the caller; the array keeps the last call's contents and nothing in it
  *    needs clearing (each call writes all it reads);
- *  - the array occupies its 4 MiB on every GPU the library runs on until the
+ *  - the array occupies its 5 MiB on every GPU the library runs on until the
  *    process ends;  MOE_ERR_LAUNCH if the array's address cannot be obtained. */
 size_t moe_gate_route_static_max_bytes(void);
 int moe_gate_route_static(const moe_shape* shape, const float* logits, const float* rts_keys_or_null,

@@ -578,7 +578,7 @@ extern "C" int moe_gate_route(const moe_shape* shape, const float* logits,
 // own copy of the array at its own address; the address is looked up once per
 // device and that pointer, never the array's name, is what host code passes on.
 // ---------------------------------------------------------------------------
-#define ROUTE_SCRATCH_BYTES (4u << 20)
+#define ROUTE_SCRATCH_BYTES (5u << 20)
 static __device__ __align__(256) unsigned char scratch[ROUTE_SCRATCH_BYTES];
 
 #define ROUTE_MAX_DEVICES 64
