@@ -98,3 +98,15 @@ def test_build_rejects_scratch_in_kernels_with_hand_issued_loads():
         bld.check_no_scratch("gate.hip", remark.format(n=28))
     # other kernels of the same file may spill
     bld.check_no_scratch("gate.hip", remark.format(n=28).replace("gate_logits_lds_kernel", "gate_dx_kernel"))
+
+
+def test_static_routing_scratch_holds_the_shape_the_header_names():
+    """moe_hip.h promises that the built-in scratch of moe_gate_route_static is enough for T = 65536, k = 2 with any
+    E <= 256.  With tiny d_model, d_ff and capacity the routing workspace is the largest one, so the general
+    workspace size is the routing workspace size (host-only calls)."""
+    B.lib()
+    cap = B.moe_gate_route_static_max_bytes()
+    for E in (2, 32, 64, 65, 128, 129, 256):
+        s = B.make_shape(65536, 8, 8, E, 2, 1, 0, 0)
+        assert 0 < B.moe_workspace_bytes(s) <= cap, E
+    assert B.moe_workspace_bytes(B.make_shape(1 << 21, 8, 8, 256, 2, 1, 0, 0)) > cap
