@@ -39,6 +39,11 @@
  *    untouched.  Non-finite logits or keys give undefined routing values but never an
  *    out-of-range index: a NaN logit counts as -inf in the top-k, and a slot that NaN
  *    keys leave unassigned is skipped by moe_dispatch.
+ *  - Index tensors that an entry point takes as input (expert_idx, slot, slot_src,
+ *    expert_count) must hold what a routing call wrote for the same shape:
+ *    0 <= expert_idx < E, -1 <= slot < capacity, -1 <= slot_src < T*k,
+ *    0 <= expert_count <= capacity.  The two dispatch calls skip an index outside
+ *    its range; the other entry points form addresses from these values unchecked.
  *  - Seeded noise (gate jitter, expert dropout) comes from the counter-based
  *    generator Philox4x32 with 10 rounds (Salmon et al., SC 2011), so a caller or
  *    a checker can reproduce every draw: element i of a tensor uses output word
