@@ -59,6 +59,9 @@ def main():
                     help="evaluation path: forward only, capacity factor 2.0, utilisation counting (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-call timings to stderr")
+    ap.add_argument("--vendor-reference", action="store_true",
+                    help="after the timed region, also time the vendor library's batched GEMM (torch.bmm) on the two "
+                         "forward products at this workload's shape (dense, plain store), for scale")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device copy (to scale rocprofv3's FETCH_SIZE/WRITE_SIZE) and exit")
     args = ap.parse_args()
@@ -293,6 +296,8 @@ def main():
         # MFMA loop on random operands sustains on this machine, and a plain copy
         out["roofline"]["frac_of_measured_mfma_random_operands"] = flops / gemm_s / 1e12 / mp["mfma_bf16_TFLOPs_random_operands"]
         out["roofline"]["frac_of_measured_copy_rate"] = ffn_bytes / gemm_s / 1e12 / mp["copy_TBps"]
+    if args.vendor_reference:
+        out["vendor_reference"] = vendor_reference(torch, w)
     if not args.no_cpu_baseline:
         del x, dy, W1, W2, layer, L
         torch.cuda.empty_cache()
@@ -310,6 +315,39 @@ def gate_skew(w, bias):
         return {"kind": "hot0", "target_top1_share": w.skew_param, "beta": float(bias[0])}
     q0 = 1.0 / sum(r ** -w.skew_param for r in range(1, w.E + 1))
     return {"kind": "zipf", "exponent": w.skew_param, "tau": float(bias.max()) / math.log(q0)}
+
+
+def vendor_reference(torch, w):
+    """The vendor library's batched GEMM on the two forward products of this workload's shape, every expert full
+    (capacity rows), bf16 in and out, no activation, no second output: what a plain library call reaches on this
+    box, for scale beside the expert GEMM's own figures.  Row-major operands as the layer holds them (no transposed
+    views).  Outside the timed region; never part of `value`."""
+    try:
+        from paper_2109_10465_amd import inputs as I
+        if w.dtype != I.BF16:
+            return {"skipped": "bf16 workloads only"}
+        E, C, d, f = w.E, w.capacity, w.d_model, w.d_ff
+        g = torch.Generator(device="cuda")
+        g.manual_seed(0)
+        mk = lambda *sh: torch.randn(*sh, device="cuda", generator=g).to(torch.bfloat16)
+        xd, h, W1, W2 = mk(E, C, d), mk(E, C, f), mk(E, d, f) * 0.02, mk(E, f, d) * 0.02
+        res = {"shape": {"E": E, "rows_per_expert": C, "d_model": d, "d_ff": f}, "library": "torch.bmm"}
+        flop = 2.0 * E * C * d * f
+        for name, fn in (("fwd1_xd_W1", lambda: torch.bmm(xd, W1)), ("fwd2_h_W2", lambda: torch.bmm(h, W2))):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) / 20 * 1e3
+            res[name] = {"us": us, "TFLOPs": flop / us / 1e6, "frac_of_mfma_peak": flop / us / 1e6 / 2500.0}
+        return res
+    except Exception as exc:      # noqa: BLE001 - report, never fail the line
+        return {"error": repr(exc)}
 
 
 def measured_peaks(torch, B):
